@@ -1,0 +1,371 @@
+"""Pins of the CPU oracle against what the paper prints and what the mathematics fixes (no GPU)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import pasa_oracle as po
+from workloads import gen_uniform_benchmark, gen_hybrid_benchmark, workload, gen_q_head, gen_kv_head
+
+
+# ------------------------------------------------------------------ rounding emulation
+
+def test_fl16_round_trip_all_bit_patterns():
+    bits = np.arange(65536, dtype=np.uint16)
+    h = bits.view(np.float16)
+    back = po.fl(h.astype(np.float64), "f16").astype(np.float16)
+    finite = np.isfinite(h)
+    assert np.array_equal(back.view(np.uint16)[finite], bits[finite])
+
+
+def test_fl16_ties_to_even_and_no_double_rounding():
+    # 4065/4096 lies exactly between 2032/2048 and 2033/2048; even significand wins.  The middle
+    # printed beta of section 2.3 depends on this tie.
+    assert po.fl(4065 / 4096, "f16") == 2032 / 2048
+    assert po.fl(4067 / 4096, "f16") == 2034 / 2048
+    # just above a tie: rounding through fp32 first would drop the 2^-30 and then tie to even (1.0)
+    assert po.fl(1 + 2.0 ** -11 + 2.0 ** -30, "f16") == 1 + 2.0 ** -10
+    assert po.fl(1 + 2.0 ** -11, "f16") == 1.0
+    # overflow boundary of Table 1: 65504 is the largest finite value, 65520 rounds to infinity
+    assert po.fl(65504.0, "f16") == 65504.0
+    assert po.fl(65519.99, "f16") == 65504.0
+    assert np.isinf(po.fl(65520.0, "f16"))
+    assert np.isneginf(po.fl(-1e6, "f16"))
+    # subnormals are kept
+    assert po.fl(2.0 ** -24, "f16") == 2.0 ** -24
+    assert po.fl(2.0 ** -26, "f16") == 0.0
+
+
+def test_fl32_matches_struct_rounding():
+    import struct
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(1000) * 10.0 ** rng.integers(-20, 20, 1000)
+    want = np.array([struct.unpack("f", struct.pack("f", v))[0] for v in x])
+    assert np.array_equal(po.fl(x, "f32"), want)
+
+
+# ------------------------------------------------------------------ optimal accuracy condition
+
+def test_optimal_beta_printed_values(golden):
+    for b0, want in golden("optimal_beta.txt"):
+        got = po.optimal_beta(float(b0), 128, "f16")
+        assert f"{got:.6f}" == want
+
+
+def test_optimal_beta_hand_derived_rationals():
+    # beta0 = 1-2^-4: b = 15/2048, fl(1-b) = 2033/2048, a = 1, f = 15 exactly
+    a, b = po._rounded_ab(1 - 2.0 ** -4, 128, "f16")
+    assert (a, b) == (1.0, 15 / 2048)
+    assert po.invariance_rounded(1 - 2.0 ** -4, 128) == 15.0
+    # beta0 = 1-2^-6: b = 63/8192, fl(1-b) = 2032/2048, a = 8191/8192, a - b n = 127/8192
+    a, b = po._rounded_ab(1 - 2.0 ** -6, 128, "f16")
+    assert (a, b) == (8191 / 8192, 63 / 8192)
+    f = po.invariance_rounded(1 - 2.0 ** -6, 128)
+    assert f == pytest.approx(8064 * 8192 / (8191 * 127) + 1 / 8191, rel=1e-14)
+    assert po.fl(f, "f16") == 63.5
+
+
+def _sig4(x):
+    return float(f"{x:.4g}")
+
+
+def test_table3_invariance(golden):
+    rows = golden("table3_invariance.txt")
+    init = [r for r in rows if r[0] == "initial"]
+    opt = [r for r in rows if r[0] == "optimized"]
+    assert len(init) == 6 and len(opt) == 6
+    for (_, b0, inva, inva1, rel), (_, bopt, invopt) in zip(init, opt):
+        b0 = float(b0)
+        ideal = b0 / (1 - b0)
+        pract = po.invariance_rounded(b0, 128, "f16")
+        assert _sig4(ideal) == float(inva)
+        assert _sig4(pract) == float(inva1)
+        assert round(100 * abs(ideal - pract) / ideal, 2) == pytest.approx(float(rel), abs=0.011)
+        b = po.optimal_beta(b0, 128, "f16")
+        # optimised beta: ideal and practical invariance coincide (Rel. Err. 0.0 %)
+        assert b / (1 - b) == pytest.approx(po.invariance_rounded(b, 128, "f16"), rel=1e-7)
+        assert _sig4(b / (1 - b)) == float(invopt)
+        digits = len(bopt.split(".")[1])
+        if bopt == "0.9":   # printed with one digit; the printed invariance fixes it
+            assert b == pytest.approx(8.971 / 9.971, abs=5e-5)
+        else:
+            assert round(b, digits) == float(bopt)
+
+
+def test_optimal_beta_bf16_is_a_fixed_point():
+    b = po.optimal_beta(1 - 2.0 ** -4, 128, "f16")
+    assert b == 0.9375
+    # generic property for another size: the solution satisfies the condition it solves
+    for n in (64, 256):
+        b = po.optimal_beta(1 - 2.0 ** -6, n, "f16")
+        assert b / (1 - b) == pytest.approx(po.invariance_rounded(b, n, "f16"), rel=1e-7)
+
+
+# ------------------------------------------------------------------ shifting-matrix algebra
+
+def test_theorem_2_1_inverse():
+    rng = np.random.default_rng(1)
+    for s in (2, 5, 128):
+        lam = rng.uniform(0, 0.9) / s
+        M = np.eye(s) - lam * np.ones((s, s))
+        Minv = np.eye(s) + lam / (1 - lam * s) * np.ones((s, s))
+        assert np.allclose(M @ Minv, np.eye(s), atol=1e-12)
+
+
+def test_shift_matrix_identities_eq_12_13_14():
+    rng = np.random.default_rng(2)
+    s2, d, beta = 16, 8, 0.9
+    alpha = math.sqrt(d)
+    Q = rng.standard_normal((5, d))
+    K = rng.standard_normal((s2, d)) + 7.0
+    M = po.shift_matrix(beta, s2, alpha)
+    # Eq. (11): K^T M = (K^T - beta Kbar^T)/alpha
+    Kp = (K.T @ M).T
+    assert np.allclose(Kp, (K - beta * K.mean(0, keepdims=True)) / alpha, atol=1e-12)
+    S = Q @ K.T / alpha
+    Sp = Q @ Kp.T
+    # Eq. (12)
+    assert np.allclose(Sp, (Q @ K.T) @ M, atol=1e-12)
+    # Eq. (13)
+    assert np.allclose(Sp @ (np.eye(s2) + beta / ((1 - beta) * s2) * np.ones((s2, s2))), S, atol=1e-11)
+    # Eq. (14)
+    assert np.allclose(Sp.mean(1) / (1 - beta), S.mean(1), atol=1e-11)
+
+
+def test_shift_keys_exact_small_integers_both_modes():
+    # integers, beta = 0.5, scale = 0.5, T = 4: every intermediate is exactly representable in fp16
+    K = np.array([[1, 2], [3, 6], [5, 2], [7, 6], [8, 0], [0, 0], [0, 8], [0, 0]], np.float16)
+    want = np.array([[-0.5, 0], [0.5, 2], [1.5, 0], [2.5, 2], [3.5, -0.5], [-0.5, -0.5], [-0.5, 3.5], [-0.5, -0.5]])
+    for mode in ("mean", "gemm_m"):
+        got = po.shift_keys(K, 0.5, 0.5, T=4, mode=mode).astype(np.float64)
+        assert np.array_equal(got, want), mode
+
+
+def test_shift_keys_modes_agree_to_rounding():
+    rng = np.random.default_rng(3)
+    K = (rng.standard_normal((256, 64)) * 3 + 40).astype(np.float16)
+    a = po.shift_keys(K, po.default_beta(), 0.125, 128, "mean").astype(np.float64)
+    b = po.shift_keys(K, 0.984497, 0.125, 128, "gemm_m").astype(np.float64)
+    # K' is O(1) while K is O(40): the rounded matrix entries perturb the removed mean by ~1e-3 relative
+    assert np.abs(a - b).max() < 0.02
+    assert np.abs(a).max() < 2.5
+
+
+def test_default_beta_invariance_is_63p5():
+    b = po.default_beta()
+    assert b / (1 - b) == pytest.approx(63.5, rel=1e-13)
+    assert po.fl(b / (1 - b), "f16") == 63.5
+    assert abs(b - 0.984497) < 2e-6
+
+
+# ------------------------------------------------------------------ golden attention
+
+def _brute_attention(Q, K, V, scale, causal, row0=0):
+    """Pure python loops, no vectorisation."""
+    R, d = Q.shape
+    N = K.shape[0]
+    out = [[0.0] * d for _ in range(R)]
+    for r in range(R):
+        nvis = min(N, row0 + r + 1) if causal else N
+        s = [scale * sum(float(Q[r, c]) * float(K[n, c]) for c in range(d)) for n in range(nvis)]
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        z = sum(e)
+        for c in range(d):
+            out[r][c] = sum(e[n] * float(V[n, c]) for n in range(nvis)) / z
+    return np.array(out)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_fp64_vs_python_loops(causal):
+    rng = np.random.default_rng(4)
+    Q = rng.standard_normal((12, 4)).astype(np.float16)
+    K = (rng.standard_normal((12, 4)) + 2).astype(np.float16)
+    V = rng.standard_normal((12, 4)).astype(np.float16)
+    got = po.attention_fp64(Q, K, V, 0.5, causal)
+    assert np.allclose(got, _brute_attention(Q, K, V, 0.5, causal), atol=1e-13)
+    # a block of rows with an offset
+    got = po.attention_fp64(Q[5:9], K, V, 0.5, causal, row0=5)
+    assert np.allclose(got, _brute_attention(Q, K, V, 0.5, causal)[5:9], atol=1e-13)
+
+
+def test_attention_fp64_vs_scipy_softmax():
+    from scipy.special import softmax
+    rng = np.random.default_rng(5)
+    Q, K, V = (rng.standard_normal((40, 16)) for _ in range(3))
+    want = softmax(Q @ K.T * 0.25, axis=1) @ V
+    assert np.allclose(po.attention_fp64(Q, K, V, 0.25, False), want, atol=1e-13)
+
+
+def test_translation_invariance_eq_9():
+    rng = np.random.default_rng(6)
+    Q, K, V = (rng.standard_normal((20, 8)) for _ in range(3))
+    k0 = rng.standard_normal((1, 8)) * 10
+    a = po.attention_fp64(Q, K, V, 0.3, False)
+    b = po.attention_fp64(Q, K - k0, V, 0.3, False)
+    assert np.allclose(a, b, atol=1e-11)
+
+
+# ------------------------------------------------------------------ Algorithm 1 algebra: exact in fp64
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("T", [2, 8, 32])
+@pytest.mark.parametrize("beta", [0.0, 0.5, 0.9375, 63.5 / 64.5])
+def test_pasa_fp64_equals_plain_definition(causal, T, beta):
+    rng = np.random.default_rng(hash((causal, T)) % 1000)
+    N, d = 96, 8
+    Q = (rng.standard_normal((N, d)) + 1.5).astype(np.float16)
+    # a bias that changes from tile to tile makes every recovery term matter
+    K = (rng.standard_normal((N, d)) + np.repeat(rng.uniform(-6, 6, N // T), T)[:, None]).astype(np.float16)
+    V = rng.standard_normal((N, d)).astype(np.float16)
+    gold = po.attention_fp64(Q, K, V, 0.35, causal)
+    info = {}
+    got = po.pasa_rows(Q, K, V, 0.35, causal, beta, T, po.EXACT64, info=info)
+    # the output is rounded to fp16 once
+    assert np.array_equal(got, gold.astype(np.float16)) or np.abs(got.astype(np.float64) - gold).max() < 1e-3
+    mism = (got != gold.astype(np.float16)).mean()
+    assert mism < 0.002      # only exact-tie flips could differ
+    assert info["s_seen"] > 0 and info["s_nonfinite"] == 0
+    # rows computed as a block with an offset give the same values
+    part = po.pasa_rows(Q[40:56], K, V, 0.35, causal, beta, T, po.EXACT64, row0=40)
+    assert np.array_equal(part, got[40:56])
+
+
+def test_pasa_fp64_gemm_m_mode_also_exact():
+    rng = np.random.default_rng(8)
+    N, d, T = 64, 8, 16
+    Q = rng.standard_normal((N, d)).astype(np.float16)
+    K = (rng.standard_normal((N, d)) + 5).astype(np.float16)
+    V = rng.standard_normal((N, d)).astype(np.float16)
+    gold = po.attention_fp64(Q, K, V, 0.35, False)
+    # beta = 0.5, T = 16, scale = 0.25: M's entries 0.25*(1-1/32) and -0.25/32 are exact in fp16, so the
+    # rounded-matrix GEMM path must still reproduce the definition up to K' rounding
+    got = po.pasa_rows(Q, K, V, 0.25, False, 0.5, T, po.EXACT64, shift="gemm_m")
+    gold = po.attention_fp64(Q, K, V, 0.25, False)
+    assert po.rmse(got, gold) < 2e-3
+
+
+def test_beta_zero_degrades_to_flash_attention():
+    rng = np.random.default_rng(9)
+    N, d, T = 256, 16, 32
+    Q = rng.standard_normal((N, d)).astype(np.float16)
+    K = rng.standard_normal((N, d)).astype(np.float16)
+    V = rng.standard_normal((N, d)).astype(np.float16)
+    for causal in (False, True):
+        gold = po.attention_fp64(Q, K, V, 0.25, causal).astype(np.float16)
+        a = po.pasa_rows(Q, K, V, 0.25, causal, 0.0, T, po.EXACT64)
+        b = po.fa_rows(Q, K, V, 0.25, causal, T, po.EXACT64)
+        assert (a != gold).mean() < 0.002 and (b != gold).mean() < 0.002
+        # scale = 0.25 is a power of two, so pre-scaling K is exact and the two mixed-precision
+        # pipelines see the same scores; they differ only in where P is rounded
+        a = po.pasa_rows(Q, K, V, 0.25, causal, 0.0, T, po.MIXED).astype(np.float64)
+        b = po.fa_rows(Q, K, V, 0.25, causal, T, po.MIXED).astype(np.float64)
+        assert np.abs(a - b).max() < 2e-3
+
+
+def test_causal_first_row_returns_first_value_exactly():
+    rng = np.random.default_rng(10)
+    Q = rng.standard_normal((256, 32)).astype(np.float16)
+    K = (rng.standard_normal((256, 32)) + 3).astype(np.float16)
+    V = rng.standard_normal((256, 32)).astype(np.float16)
+    for pol in (po.MIXED, po.STRICT16):
+        out = po.pasa_rows(Q, K, V, 0.2, True, po.default_beta(), 128, pol)
+        assert np.array_equal(out[0], V[0])
+
+
+def test_single_tile_low_precision_close_to_definition():
+    rng = np.random.default_rng(11)
+    Q = rng.standard_normal((64, 64)).astype(np.float16)
+    K = (rng.standard_normal((128, 64)) + 4).astype(np.float16)
+    V = rng.standard_normal((128, 64)).astype(np.float16)
+    gold = po.attention_fp64(Q, K, V, 0.125, False)
+    # with one tile no recovery term is ever applied: accuracy is that of fp16 operands alone
+    assert po.rmse(po.pasa_rows(Q, K, V, 0.125, False, po.default_beta(), 128, po.MIXED), gold) < 1e-3
+    assert po.rmse(po.pasa_rows(Q, K, V, 0.125, False, po.default_beta(), 128, po.STRICT16), gold) < 2e-3
+
+
+def test_gqa_head_mapping():
+    rng = np.random.default_rng(12)
+    q = rng.standard_normal((1, 4, 128, 16)).astype(np.float16)
+    k = rng.standard_normal((1, 2, 128, 16)).astype(np.float16)
+    v = rng.standard_normal((1, 2, 128, 16)).astype(np.float16)
+    g = po.attention_fp64_bhnd(q, k, v, 0.25, True, block=48)
+    for h in range(4):
+        assert np.allclose(g[0, h], po.attention_fp64(q[0, h], k[0, h // 2], v[0, h // 2], 0.25, True), atol=1e-12)
+    o = po.pasa_bhnd(q, k, v, 0.25, True, 0.9375, 128, po.MIXED)
+    assert np.array_equal(o[0, 3], po.pasa_rows(q[0, 3], k[0, 1], v[0, 1], 0.25, True, 0.9375, 128, po.MIXED))
+
+
+def test_rmse_closed_form():
+    g = np.array([[3.0, 4.0]])
+    assert po.rmse(g * 1.1, g) == pytest.approx(0.1)
+    assert po.rmse(g, g) == 0.0
+
+
+# ------------------------------------------------------------------ overflow behaviour the paper reports
+
+@pytest.mark.parametrize("row", [1, 4])
+def test_table4_full_nan_rows(row, golden):
+    r = [x for x in golden("table4_nan.txt") if int(x[0]) == row][0]
+    dist, x0, am, pct = r[1], float(r[2]), float(r[3]), float(r[4])
+    assert pct == 100
+    gen = gen_uniform_benchmark if dist == "uniform" else gen_hybrid_benchmark
+    q, k, v = gen(x0, am, seed=row, shape=(1, 2, 1280, 128))
+    scale = 1 / math.sqrt(128)
+    # closed form: E[q.k] = 128 * x0^2 = 115200 > 65504, so every raw score overflows fp16
+    info = {}
+    o = po.fa_rows(q[0, 0], k[0, 0], v[0, 0], scale, False, 128, po.PARTIAL16, info=info)
+    assert info["s_nonfinite"] == info["s_seen"]
+    assert np.isnan(o).all()
+    gold = po.attention_fp64(q[0, 1], k[0, 1], v[0, 1], scale, False)
+    for pol in (po.MIXED, po.STRICT16):
+        info = {}
+        o = po.pasa_rows(q[0, 1], k[0, 1], v[0, 1], scale, False, po.default_beta(), 128, pol, info=info)
+        assert np.isfinite(o).all() and info["s_nonfinite"] == 0 and info["smax"] < po.FP16_MAX / 50
+        assert po.rmse(o, gold) < 0.05
+    # the fp32 allocation does not overflow either (Appendix D)
+    assert np.isfinite(po.fa_rows(q[0, 1], k[0, 1], v[0, 1], scale, False, 128, po.MIXED)).all()
+
+
+def test_table4_partial_overflow_rows_are_partial(golden):
+    # rows 2, 3 (uniform, x0 = 20): seed dependent, so only "some but not all outputs are NaN, and more
+    # for the larger amplitude" is checked, as the table shows (0.12 % < 8.14 %)
+    scale = 1 / math.sqrt(128)
+    frac = {}
+    for am in (15.0, 20.0):
+        q, k, v = gen_uniform_benchmark(20.0, am, seed=2, shape=(1, 1, 1280, 128))
+        o = po.fa_rows(q[0, 0], k[0, 0], v[0, 0], scale, False, 128, po.PARTIAL16)
+        frac[am] = float(np.isnan(o).mean())
+        assert np.isfinite(po.pasa_rows(q[0, 0], k[0, 0], v[0, 0], scale, False, po.default_beta(), 128, po.STRICT16)).all()
+    assert 0.0 < frac[15.0] < frac[20.0] < 0.5
+
+
+def test_overflow_workload_naive_overflows_pasa_does_not():
+    w = workload("overflow_bias").with_n(512)
+    q = gen_q_head(w, 0, 0)
+    k, v = gen_kv_head(w, 0, 0)
+    info = {}
+    o = po.fa_rows(q, k, v, w.scale, False, 128, po.PARTIAL16, info=info)
+    assert info["s_nonfinite"] == info["s_seen"] and np.isnan(o).all()
+    info = {}
+    o = po.pasa_rows(q, k, v, w.scale, False, po.default_beta(), 128, po.STRICT16, info=info)
+    assert np.isfinite(o).all() and info["smax"] < 400
+
+
+def test_rmse_ordering_nonzero_mean():
+    # Appendix D: for non-zero-mean inputs without overflow, RMSE(fp32 FA) < RMSE(PASA) < RMSE(FP16-FP32 FA).
+    # The plotted values are lost, so only the ordering is checked.  It holds when PASA's score tile is
+    # fp16 and its per-row statistics are fp32 (and for MIXED); with fp16 statistics the x63.5 recovery
+    # factor amplifies the rounding of Sbar' and the all-fp16 policy lands above the FP16-FP32 baseline
+    # on this generator -- measured and recorded, not asserted.
+    q, k, v = gen_uniform_benchmark(20.0, 0.5, seed=7, shape=(1, 1, 1280, 128))
+    scale = 1 / math.sqrt(128)
+    Q, K, V = q[0, 0], k[0, 0], v[0, 0]
+    gold = po.attention_fp64(Q, K, V, scale, False)
+    e32 = po.rmse(po.fa_rows(Q, K, V, scale, False, 128, po.MIXED), gold)
+    e16 = po.rmse(po.fa_rows(Q, K, V, scale, False, 128, po.PARTIAL16), gold)
+    for pol in (po.PARTIAL16, po.MIXED):
+        epasa = po.rmse(po.pasa_rows(Q, K, V, scale, False, po.default_beta(), 128, pol), gold)
+        assert e32 < epasa < e16, (pol, e32, epasa, e16)
+    estrict = po.rmse(po.pasa_rows(Q, K, V, scale, False, po.default_beta(), 128, po.STRICT16), gold)
+    assert estrict < 0.02
