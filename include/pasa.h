@@ -1,0 +1,111 @@
+/*
+ * libpasa -- PASA (online pseudo-average shifting attention, arXiv 2503.01873) forward pass for
+ * AMD MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ types, no exceptions.
+ *
+ * What is computed (paper section 1.1 problem statement, Algorithm 1):
+ *     O = softmax(scale * Q K^T) V      per (batch, query head), optionally causal,
+ * evaluated FlashAttention-style over key tiles of 128 keys.  Each key tile is shifted by beta times
+ * its own mean along the sequence and scaled (Eq. (10), (11)), which leaves every softmax row unchanged
+ * (Eq. (9)); a per-row global recovering step re-aligns the running maximum, sum and output across
+ * tiles (Eq. (13)-(15), Algorithm 1 steps 1-4) so that half-precision scores stay far below 65504.
+ *
+ * Layouts.  q, o: [B, Hq, N, d];  k, v: [B, Hkv, N, d].  IEEE fp16, row-major, contiguous, DEVICE
+ * pointers, 16-byte aligned.  Query head h reads KV head h / (Hq / Hkv) (grouped-query attention; the
+ * paper does not discuss it).  causal != 0: key n is visible to query r iff n <= r.
+ *
+ * Ownership.  The caller owns every buffer, including the workspace.  The library keeps no device
+ * state between calls.  q, k, v are only read; o is only written and must not alias an input.
+ *
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default stream).  Every entry point
+ * only enqueues work and returns; it never synchronises the device.
+ *
+ * Errors.  Every function returning int returns a pasa_status.  All argument checking happens on the
+ * host before anything is enqueued; on error nothing has been launched.
+ */
+#ifndef PASA_H
+#define PASA_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PASA_OK = 0,
+    PASA_EINVAL = 1,       /* null or misaligned pointer, non-positive size, Hq % Hkv != 0, bad scale / beta / variant */
+    PASA_EUNSUPPORTED = 2, /* d not in {64, 128}, N not a multiple of 128, N > 262144, shift_tile != 128 */
+    PASA_ELAUNCH = 3,      /* the HIP runtime refused an allocation or a launch */
+    PASA_EWORKSPACE = 4    /* workspace missing, misaligned or smaller than pasa_attn_fwd_workspace() */
+} pasa_status;
+
+/* Precision allocation of the tile loop (paper section 1.2).  The matrix cores always accumulate in
+ * fp32; "fp16" below means the value is rounded to fp16 (nearest-even) where Algorithm 1 marks it. */
+typedef enum {
+    PASA_MIXED = 0,    /* K' and P fp16 (the GEMM operands); S', row statistics and O fp32 */
+    PASA_STRICT16 = 1, /* Algorithm 1 as printed: S', P, Sbar', F, all Delta terms, m, l, P V and O rounded to fp16 */
+    PASA_NAIVE16 = 2,  /* no shift (beta forced to 0): raw S = Q K^T rounded to fp16, then scaled; rest fp32.
+                          This is the partially low-precision FlashAttention that overflows (section 2.1, Table 4). */
+    PASA_S16 = 3       /* shifted like MIXED, S' rounded to fp16 as it leaves the matrix core, statistics and O fp32 */
+} pasa_variant;
+
+typedef struct {
+    float beta;        /* shift fraction of Eq. (10).  < 0: library default 63.5/64.5 (invariance beta/(1-beta) = 63.5,
+                          the fp16 value of the invariance of the paper's adopted beta = 0.984497);  0: plain FlashAttention;
+                          otherwise must lie in [0, 1). */
+    int variant;       /* a pasa_variant */
+    int shift_tile;    /* keys per pseudo-average group; 0 or 128 (the only supported size) */
+    unsigned long long* overflow_s;  /* optional DEVICE counter (caller zeroes it): score-tile entries whose magnitude
+                                        exceeds 65504 where they would be stored as fp16.  NULL: not counted. */
+    unsigned long long* nonfinite_o; /* optional DEVICE counter (caller zeroes it): inf/NaN entries written to o. */
+} pasa_opts;
+
+/* Default configuration: PASA_MIXED, default beta.  Allocates and frees its workspace in stream order
+ * (hipMallocAsync / hipFreeAsync).  scale multiplies Q K^T (normally 1/sqrt(d)); finite and > 0. */
+int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
+                  int B, int Hq, int Hkv, int N, int d, int causal, float scale, void* stream);
+
+/* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes (shifted keys K' and re-tiled values,
+ * both fp16: 4*B*Hkv*N*d bytes).  Returns 0 if the sizes are invalid. */
+size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
+
+/* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
+ * at least pasa_attn_fwd_workspace() bytes; contents on return are unspecified).  opts == NULL means
+ * {beta = -1, PASA_MIXED, 128, NULL, NULL}.  Performs no allocation. */
+int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
+                     int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                     const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The two halves of pasa_attn_fwd_ex as separate calls, for callers that attend to the same keys and
+ * values more than once (several query chunks against one K/V): pasa_prepare_kv runs Algorithm 1's
+ * pre-processing loop (key shift, Eq. (11)) and re-tiles K' and V into `workspace`;
+ * pasa_attn_fwd_prepared runs the main loops of Algorithm 1 against such a workspace.  Both calls must be
+ * given the same B, Hkv, N, d, scale and opts (beta, variant); pasa_attn_fwd_prepared does not read k or v.
+ * Same argument rules, workspace size and error codes as pasa_attn_fwd_ex. */
+int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, float scale,
+                    const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
+int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                           const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
+
+/* Key pre-processing alone (Algorithm 1's first loop, Eq. (11)): writes, for every 128-key tile,
+ * K'[n, c] = fp16((K[n, c] - beta * mean_tile(K[:, c])) * kscale) to kprime in the plain [B, Hkv, N, d]
+ * layout.  The mean and the arithmetic are fp64 and the result is rounded once.  For tests and tools;
+ * the attention entry points do this internally in their own tiled layout. */
+int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d,
+                    double beta, double kscale, void* stream);
+
+/* Host-only, fp64: solves the optimal accuracy condition beta/(1-beta) = f(beta) (Eq. (16), (20)-(22)) by
+ * fixed-point iteration from beta0, for a shifting matrix of size n rounded to format tp
+ * (0 = fp16, 1 = bf16).  Returns NaN for invalid arguments. */
+double pasa_optimal_beta(double beta0, int n, int tp);
+
+/* Host-only: the practical invariance Inva_1 of Eq. (20) for the given beta. */
+double pasa_invariance_rounded(double beta, int n, int tp);
+
+const char* pasa_status_string(int status);
+int pasa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PASA_H */

@@ -1,0 +1,238 @@
+// libpasa host layer: the C ABI declared in include/pasa.h.
+// Argument validation, the optimal-beta solve (host, fp64) and kernel dispatch.  No device code here.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "pasa.h"
+#include "pasa_kernels.h"
+
+namespace {
+
+constexpr int kShiftTile = 128;
+constexpr int kMaxN = 262144;   // tile counters stay exactly representable in fp16 (STRICT16 statistics)
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Round x to a binary floating-point format with `prec` significand bits (including the hidden one),
+// minimum normal exponent emin and maximum exponent emax (value < 2^(emax+1)); ties to even; gradual
+// underflow; overflow to infinity.  fp16: (11, -14, 15).  bf16: (8, -126, 127).
+double round_to_format(double x, int prec, int emin, int emax)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    frexp(x, &e);            // x = m * 2^e with 0.5 <= |m| < 1, so the leading bit has weight 2^(e-1)
+    int lsb = e - prec;      // weight of the last kept bit
+    if (lsb < emin - (prec - 1)) lsb = emin - (prec - 1);   // subnormal range: fixed spacing
+    const double r = ldexp(nearbyint(ldexp(x, -lsb)), lsb); // nearbyint: ties to even in the default mode
+    if (fabs(r) >= ldexp(1.0, emax + 1)) return copysign(INFINITY, x);
+    return r;
+}
+
+double fl_tp(double x, int tp) { return tp == 0 ? round_to_format(x, 11, -14, 15) : round_to_format(x, 8, -126, 127); }
+
+// Eq. (20), (21): the invariance the rounded shifting matrix a*I - b*J really has.
+double invariance_rounded(double beta, int n, int tp)
+{
+    const double b = fl_tp(beta / n, tp);
+    const double a = fl_tp(1.0 - beta / n, tp) + b;
+    return b * n / (a * (a - b * n)) + (1.0 - a) / a;
+}
+
+int check_shape(int B, int Hq, int Hkv, int N, int d)
+{
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0) return PASA_EINVAL;
+    if (Hq % Hkv != 0) return PASA_EINVAL;
+    if (d != 64 && d != 128) return PASA_EUNSUPPORTED;
+    if (N % kShiftTile != 0 || N > kMaxN) return PASA_EUNSUPPORTED;
+    return PASA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pasa_status_string(int status)
+{
+    switch (status) {
+        case PASA_OK: return "ok";
+        case PASA_EINVAL: return "invalid argument";
+        case PASA_EUNSUPPORTED: return "unsupported size (d must be 64 or 128, N a multiple of 128 and <= 262144, shift tile 128)";
+        case PASA_ELAUNCH: return "HIP runtime refused an allocation or a kernel launch";
+        case PASA_EWORKSPACE: return "workspace missing, misaligned or too small";
+        default: return "unknown status";
+    }
+}
+
+int pasa_version(void) { return 100; }
+
+double pasa_invariance_rounded(double beta, int n, int tp)
+{
+    if (!(beta >= 0.0) || !(beta < 1.0) || n <= 0 || (tp != 0 && tp != 1)) return NAN;
+    return invariance_rounded(beta, n, tp);
+}
+
+double pasa_optimal_beta(double beta0, int n, int tp)
+{
+    if (!(beta0 > 0.0) || !(beta0 < 1.0) || n <= 0 || (tp != 0 && tp != 1)) return NAN;
+    double beta = beta0;
+    for (int it = 0; it < 1000; ++it) {          // Eq. (22): beta <- f/(1+f)
+        const double f = invariance_rounded(beta, n, tp);
+        const double next = f / (1.0 + f);
+        const double err = fabs(next - beta) / fabs(beta);
+        beta = next;
+        if (err <= 1e-8) break;
+    }
+    return beta;
+}
+
+size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
+{
+    if (check_shape(B, Hq, Hkv, N, d) != PASA_OK) return 0;
+    return (size_t)4 * (size_t)B * (size_t)Hkv * (size_t)N * (size_t)d;
+}
+
+int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale, void* stream)
+{
+    const int st = check_shape(B, Hkv, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    if (k == nullptr || kprime == nullptr || !aligned(k, 16) || !aligned(kprime, 16) || k == kprime) return PASA_EINVAL;
+    if (!(beta >= 0.0) || !(beta < 1.0) || !isfinite(kscale) || !(kscale > 0.0)) return PASA_EINVAL;
+    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, nullptr, kprime, B, Hkv, N, d, beta, kscale,
+                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
+namespace {
+
+// Resolved numeric parameters of one call.
+struct Params {
+    int variant;
+    double beta;      // shift fraction used by the pre-processing kernel
+    double kscale;    // factor folded into K'
+    float inva;       // beta/(1-beta) rounded to the statistics precision
+    unsigned long long* overflow_s;
+    unsigned long long* nonfinite_o;
+};
+
+int resolve(const pasa_opts* opts, float scale, Params* out)
+{
+    if (!isfinite(scale) || !(scale > 0.f)) return PASA_EINVAL;
+    pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr};
+    if (opts != nullptr) op = *opts;
+    if (op.variant < PASA_MIXED || op.variant > PASA_S16) return PASA_EINVAL;
+    if (op.shift_tile != 0 && op.shift_tile != kShiftTile) return PASA_EUNSUPPORTED;
+    if (!(op.beta < 1.f)) return PASA_EINVAL;              // also rejects NaN
+    // beta and the invariance beta/(1-beta) in fp64; the default makes the invariance exactly 63.5
+    double beta = op.beta < 0.f ? 63.5 / 64.5 : (double)op.beta;
+    double kscale = (double)scale;
+    if (op.variant == PASA_NAIVE16) {   // no shift, static scaling applied after the first GEMM (Eq. (1), (2))
+        beta = 0.0;
+        kscale = 1.0;
+    }
+    const double inva_d = beta / (1.0 - beta);
+    out->variant = op.variant;
+    out->beta = beta;
+    out->kscale = kscale;
+    out->inva = op.variant == PASA_STRICT16 ? (float)round_to_format(inva_d, 11, -14, 15) : (float)inva_d;
+    out->overflow_s = op.overflow_s;
+    out->nonfinite_o = op.nonfinite_o;
+    return PASA_OK;
+}
+
+int check_workspace(const void* ws, size_t bytes, size_t need)
+{
+    return (ws == nullptr || !aligned(ws, 256) || bytes < need) ? PASA_EWORKSPACE : PASA_OK;
+}
+
+}  // namespace
+
+int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, float scale, const pasa_opts* opts,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (k == nullptr || v == nullptr || !aligned(k, 16) || !aligned(v, 16)) return PASA_EINVAL;
+    Params pr;
+    int st = resolve(opts, scale, &pr);
+    if (st != PASA_OK) return st;
+    st = check_shape(B, Hkv, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    const size_t need = pasa_attn_fwd_workspace(B, Hkv, Hkv, N, d);
+    st = check_workspace(workspace, workspace_bytes, need);
+    if (st != PASA_OK) return st;
+    char* ws = static_cast<char*>(workspace);
+    const hipError_t e = pasa_launch_prep(k, v, ws, ws + need / 2, nullptr, B, Hkv, N, d, pr.beta, pr.kscale,
+                                          static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
+int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                           const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (q == nullptr || o == nullptr || !aligned(q, 16) || !aligned(o, 16) || o == q) return PASA_EINVAL;
+    if (causal != 0 && causal != 1) return PASA_EINVAL;
+    Params pr;
+    int st = resolve(opts, scale, &pr);
+    if (st != PASA_OK) return st;
+    st = check_shape(B, Hq, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
+    st = check_workspace(workspace, workspace_bytes, need);
+    if (st != PASA_OK) return st;
+    const char* ws = static_cast<const char*>(workspace);
+    PasaLaunch p;
+    p.q = q; p.kp = ws; p.vt = ws + need / 2; p.o = o;
+    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.d = d;
+    p.causal = causal;
+    p.variant = pr.variant;
+    p.inva = pr.inva;
+    p.scale = scale;
+    p.overflow_s = pr.overflow_s;
+    p.nonfinite_o = pr.nonfinite_o;
+    p.stream = static_cast<hipStream_t>(stream);
+    return pasa_launch_fwd(p) == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
+int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N, int d,
+                     int causal, float scale, const pasa_opts* opts, void* workspace, size_t workspace_bytes,
+                     void* stream)
+{
+    // all checks of both halves first, so that nothing is enqueued on error
+    if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return PASA_EINVAL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16)) return PASA_EINVAL;
+    if (o == q || o == k || o == v) return PASA_EINVAL;
+    if (causal != 0 && causal != 1) return PASA_EINVAL;
+    Params pr;
+    int st = resolve(opts, scale, &pr);
+    if (st != PASA_OK) return st;
+    st = check_shape(B, Hq, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    st = check_workspace(workspace, workspace_bytes, pasa_attn_fwd_workspace(B, Hq, Hkv, N, d));
+    if (st != PASA_OK) return st;
+    st = pasa_prepare_kv(k, v, B, Hkv, N, d, scale, opts, workspace, workspace_bytes, stream);
+    if (st != PASA_OK) return st;
+    return pasa_attn_fwd_prepared(q, o, B, Hq, Hkv, N, d, causal, scale, opts, workspace, workspace_bytes, stream);
+}
+
+int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N, int d,
+                  int causal, float scale, void* stream)
+{
+    // validate before allocating anything: run the checks of the _ex entry point against a dummy workspace size
+    const int st = check_shape(B, Hq, Hkv, N, d);
+    if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return PASA_EINVAL;
+    if (st != PASA_OK) return st;
+    const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    void* ws = nullptr;
+    if (hipMallocAsync(&ws, need, s) != hipSuccess || ws == nullptr) {
+        (void)hipGetLastError();
+        return PASA_ELAUNCH;
+    }
+    const int rc = pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, nullptr, ws, need, stream);
+    if (hipFreeAsync(ws, s) != hipSuccess) {
+        (void)hipGetLastError();
+        return rc == PASA_OK ? PASA_ELAUNCH : rc;
+    }
+    return rc;
+}
+
+}  // extern "C"

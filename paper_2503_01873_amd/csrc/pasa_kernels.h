@@ -1,0 +1,32 @@
+// Internal interface between the C-ABI host layer and the device code.  Not installed.
+#ifndef PASA_KERNELS_H
+#define PASA_KERNELS_H
+
+#include <hip/hip_runtime.h>
+
+// kernel precision variants; values equal the public pasa_variant enumerators
+enum { PASA_K_MIXED = 0, PASA_K_STRICT16 = 1, PASA_K_NAIVE16 = 2, PASA_K_S16 = 3 };
+
+struct PasaLaunch {
+    const void* q;
+    const void* kp;   // shifted keys, tiled layout
+    const void* vt;   // values, tiled layout
+    void* o;
+    int B, Hq, Hkv, N, d;
+    int causal;
+    int variant;
+    float inva;       // beta/(1-beta), already rounded to the statistics precision
+    float scale;      // only used by PASA_K_NAIVE16 (static scaling after the first GEMM)
+    unsigned long long* overflow_s;
+    unsigned long long* nonfinite_o;
+    hipStream_t stream;
+};
+
+// Shift + re-tile K (and re-tile V when v != nullptr).  plain_out != nullptr: K' goes there in the
+// plain [B,Hkv,N,d] layout and kp / vt are not written.
+hipError_t pasa_launch_prep(const void* k, const void* v, void* kp, void* vt, void* plain_out,
+                            int B, int Hkv, int N, int d, double beta, double kscale, hipStream_t stream);
+
+hipError_t pasa_launch_fwd(const PasaLaunch& p);
+
+#endif

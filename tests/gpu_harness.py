@@ -1,0 +1,51 @@
+"""Helpers for the GPU parity tests: move seeded inputs to the device, call the C ABI, fetch results.
+torch is used for device memory and streams only."""
+from __future__ import annotations
+
+import numpy as np
+
+import paper_2503_01873_amd as P
+from oracle import pasa_oracle as po
+
+ORACLE_POLICY = {P.MIXED: po.MIXED, P.STRICT16: po.STRICT16, P.S16: po.PARTIAL16}
+VARIANT_NAME = {P.MIXED: "MIXED", P.STRICT16: "STRICT16", P.NAIVE16: "NAIVE16", P.S16: "S16"}
+
+
+def f32(x: float) -> float:
+    """The value a C float argument will carry."""
+    return float(np.float32(x))
+
+
+def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False, entry="ex"):
+    """Run the HIP path on numpy fp16 inputs [B,H,N,d]; returns (o fp16 numpy, counters or None)."""
+    import torch
+    dev = torch.device("cuda:0")
+    B, Hq, N, d = q.shape
+    Hkv = k.shape[1]
+    tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (q, k, v))
+    to = torch.full_like(tq, float("nan"))
+    cnt = torch.zeros(2, dtype=torch.int64, device=dev) if counters else None
+    stream = torch.cuda.current_stream()
+    if entry == "plain":
+        P.pasa_attn_fwd(tq, tk, tv, to, B, Hq, Hkv, N, d, causal, scale, stream)
+    else:
+        wsb = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
+        ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+        kw = dict(beta=beta, variant=variant)
+        if entry == "ex":
+            P.pasa_attn_fwd_ex(tq, tk, tv, to, B, Hq, Hkv, N, d, causal, scale, ws, wsb, stream,
+                               overflow_s=cnt[0:1] if counters else None,
+                               nonfinite_o=cnt[1:2] if counters else None, **kw)
+        elif entry == "split":
+            P.pasa_prepare_kv(tk, tv, B, Hkv, N, d, scale, ws, wsb, stream, **kw)
+            P.pasa_attn_fwd_prepared(tq, to, B, Hq, Hkv, N, d, causal, scale, ws, wsb, stream, **kw)
+        else:
+            raise ValueError(entry)
+    torch.cuda.synchronize()
+    return to.cpu().numpy(), (cnt.cpu().numpy() if counters else None)
+
+
+def compare(o, ref):
+    d = np.abs(o.astype(np.float64) - ref.astype(np.float64))
+    return dict(maxabs=float(d.max()), p999=float(np.quantile(d, 0.999)), p99=float(np.quantile(d, 0.99)),
+                mismatch=float((o != ref).mean()))
