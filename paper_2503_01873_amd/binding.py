@@ -12,7 +12,7 @@ import os
 MIXED, STRICT16, NAIVE16, S16 = 0, 1, 2, 3
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "libpasa.so")
+_LIB_PATH = os.environ.get("PASA_LIB") or os.path.join(_PKG, "libpasa.so")
 _lib = None
 
 

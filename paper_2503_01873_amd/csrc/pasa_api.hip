@@ -98,7 +98,7 @@ int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d, d
     if (st != PASA_OK) return st;
     if (k == nullptr || kprime == nullptr || !aligned(k, 16) || !aligned(kprime, 16) || k == kprime) return PASA_EINVAL;
     if (!(beta >= 0.0) || !(beta < 1.0) || !isfinite(kscale) || !(kscale > 0.0)) return PASA_EINVAL;
-    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, nullptr, kprime, B, Hkv, N, d, beta, kscale,
+    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, beta, kscale,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
@@ -159,8 +159,7 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
     const size_t need = pasa_attn_fwd_workspace(B, Hkv, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
-    char* ws = static_cast<char*>(workspace);
-    const hipError_t e = pasa_launch_prep(k, v, ws, ws + need / 2, nullptr, B, Hkv, N, d, pr.beta, pr.kscale,
+    const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
@@ -178,9 +177,8 @@ int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N
     const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
-    const char* ws = static_cast<const char*>(workspace);
     PasaLaunch p;
-    p.q = q; p.kp = ws; p.vt = ws + need / 2; p.o = o;
+    p.q = q; p.ws = workspace; p.o = o;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.d = d;
     p.causal = causal;
     p.variant = pr.variant;

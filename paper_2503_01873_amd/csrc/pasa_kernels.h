@@ -9,8 +9,7 @@ enum { PASA_K_MIXED = 0, PASA_K_STRICT16 = 1, PASA_K_NAIVE16 = 2, PASA_K_S16 = 3
 
 struct PasaLaunch {
     const void* q;
-    const void* kp;   // shifted keys, tiled layout
-    const void* vt;   // values, tiled layout
+    const void* ws;   // per (batch, KV head, key tile): shifted-key tile then value tile, fragment-major layout
     void* o;
     int B, Hq, Hkv, N, d;
     int causal;
@@ -23,8 +22,8 @@ struct PasaLaunch {
 };
 
 // Shift + re-tile K (and re-tile V when v != nullptr).  plain_out != nullptr: K' goes there in the
-// plain [B,Hkv,N,d] layout and kp / vt are not written.
-hipError_t pasa_launch_prep(const void* k, const void* v, void* kp, void* vt, void* plain_out,
+// plain [B,Hkv,N,d] layout and ws is not written.
+hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);

@@ -16,7 +16,9 @@
 //                 statistics (pseudo-average Sbar', maximum m', sum l') are in-lane reductions plus one exchange
 //                 with lane^32, and exp(S'-m') converted to fp16 is already the B operand of the second GEMM.
 //
-// Tile layouts in the workspace (one tile = 128 keys x D channels, fp16, 16-byte chunks):
+// Workspace: for every (batch, KV head, key tile) the K' tile followed by the V tile, so that one tile pair is
+// one contiguous block that is copied to LDS verbatim with direct global->LDS loads, double buffered.
+// Tile layouts (one tile = 128 keys x D channels, fp16, 16-byte chunks):
 //   K' tile: chunk index (c/8)*128 + n         holds channels 8*(c/8) .. +7 of key n
 //   V  tile: chunk index ((n/16)*2 + h)*D + c  holds, for channel c, the 8 keys 16*(n/16) + {4h..4h+3, 8+4h..8+4h+3}
 // The second layout is the key order in which a lane of the 32x32 accumulator holds its S'^T rows.
@@ -37,9 +39,6 @@ typedef float f2 __attribute__((ext_vector_type(2)));
 namespace {
 
 constexpr int T = 128;          // keys per shift tile (s2 of the paper)
-constexpr int ROWS_PER_WAVE = 64;
-constexpr int WAVES = 4;
-constexpr int ROWS_PER_WG = ROWS_PER_WAVE * WAVES;
 constexpr float LOG2E = 1.4426950408889634f;
 
 // ---------------------------------------------------------------------------------------------
@@ -65,7 +64,7 @@ __device__ inline _Float16 double_to_half_rn(double x)
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
-                                                    _Float16* __restrict__ kp, _Float16* __restrict__ vt,
+                                                    _Float16* __restrict__ wsout,
                                                     _Float16* __restrict__ plain_out, double beta, double kscale)
 {
     constexpr int CH = D / 8;            // 16-byte chunks per key
@@ -122,11 +121,11 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
         if (plain_out != nullptr)
             *reinterpret_cast<h8*>(plain_out + tile * (size_t)(T * D) + n * D + 8 * c8) = out;
         else
-            *reinterpret_cast<h8*>(kp + tile * (size_t)(T * D) + ((size_t)c8 * T + n) * 8) = out;
+            *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)c8 * T + n) * 8) = out;
     }
 
     if (v != nullptr) {
-        _Float16* vdst = vt + tile * (size_t)(T * D);
+        _Float16* vdst = wsout + tile * (size_t)(2 * T * D) + T * D;
         for (int chunk = tid; chunk < 16 * D; chunk += 256) {
             const int c = chunk % D;
             const int kh = chunk / D;            // (n/16)*2 + h
@@ -146,23 +145,72 @@ __device__ inline float xor32(float x) { return __shfl_xor(x, 32, 64); }
 
 __device__ inline float exp_nat(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
 
+__device__ inline h2 pack_rn(float a, float b)
+{
+    const f2 v = {a, b};
+    return __builtin_convertvector(v, h2);     // v_cvt_pk_f16_f32: nearest-even
+}
+
+// a + b + acc with the two halves widened exactly (v_dot2_f32_f16 against ones)
+__device__ inline float add_pair(h2 v, float acc)
+{
+    const h2 one = {(_Float16)1, (_Float16)1};
+    return __builtin_amdgcn_fdot2(v, one, acc, false);
+}
+
+// One wave-wide direct global -> LDS copy of 1 KiB: lane i moves 16 bytes from gsrc + 16*i to ldst + 16*i.
+// ldst must be wave-uniform (it travels in M0).
+__device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc + lane * 16),
+                                     (__attribute__((address_space(3))) void*)ldst, 16, 0, 0);
+}
+
+#define PASA_FENCE() __builtin_amdgcn_sched_barrier(0)
+#ifndef PASA_PRE
+#define PASA_PRE 1
+#endif
+
+// A workgroup is 8 wavefronts and owns 256 query rows, 32 per wavefront.  Wavefronts 0-3 (group A) and 4-7
+// (group B) sit pairwise on the four SIMDs and run the same program half a tile apart: time is cut into slots
+// separated by workgroup barriers, and in every slot one group is in its matrix part (second GEMM of the previous
+// tile, first GEMM of the next) while the other is in its vector part (softmax statistics, global recovering,
+// output rescale), so the MFMA pipe and the VALU of a SIMD are busy at the same time.
+//
+//   group A:  M(0) V(0) M(1) V(1) ...        group B:  -  M(0) V(0) M(1) ...
+//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]      V(j) = [ statistics, P(j), recovery, rescale ]
+//
+// LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued two slots ahead.
+//
+// Output accumulation.  STRICT16 keeps Algorithm 1's form: the tile product is rounded to fp16 and combined as
+// O = fp16(e^{dm_j} * PV) + fp16(e^{dm_{j-1}} * O).  The fp32 variants accumulate the second GEMM directly onto the
+// running output, which is stored relative to the level of the tile that was added last: with c_j = e^{dm_j},
+// O_j = c_j * Ostore_j and Ostore_j = P_j V_j + g_j * Ostore_{j-1}, g_j = e^{dm_{j-1}} * c_{j-1} / c_j.  P_j itself is
+// the paper's exp(S' - m'_j) rounded to fp16, so the GEMM operands are those of Algorithm 1 and only fp32 rounding
+// order differs.  A tile whose level lies more than 60 below the running maximum cannot change an fp32 output
+// and is dropped for that row (P row zeroed), which keeps g_j <= e^60.
 template <int D, int VAR, bool CAUSAL, bool INSTR>
-__global__ __launch_bounds__(256, 1) void pasa_fwd(const _Float16* __restrict__ q, const _Float16* __restrict__ kp,
-                                                   const _Float16* __restrict__ vt, _Float16* __restrict__ o,
-                                                   int Hq, int Hkv, int N, int nqt, float inva, float scale,
-                                                   unsigned long long* ovf_s, unsigned long long* nonfinite_o)
+__global__ __launch_bounds__(512, 2)
+void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
+              int Hq, int Hkv, int N, int nqt, float inva, float scale,
+              unsigned long long* ovf_s, unsigned long long* nonfinite_o)
 {
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
     constexpr int CB = D / 32;   // 32-channel row blocks of O^T
     constexpr bool S16 = (VAR != PASA_K_MIXED);                 // S' rounded to fp16 as it leaves the matrix core
     constexpr bool STRICT = (VAR == PASA_K_STRICT16);
     constexpr bool NAIVE = (VAR == PASA_K_NAIVE16);
-    constexpr int TILE_HALFS = T * D;
+    constexpr int KT_BYTES = T * D * 2;                         // one K' (or V) tile
+    constexpr int TILE_BYTES = 2 * KT_BYTES;                    // workspace stride: K' tile then V tile
+    constexpr int CPW = KT_BYTES / 1024 / 8;                    // 1 KiB copies per wave per K' (or V) tile
+    constexpr int RW = 32, RWG = 256;
+    constexpr int PRE = PASA_PRE;                               // k-steps of LDS fragments in flight
 
-    __shared__ __attribute__((aligned(16))) _Float16 lds_k[TILE_HALFS];
-    __shared__ __attribute__((aligned(16))) _Float16 lds_v[TILE_HALFS];
+    extern __shared__ __attribute__((aligned(1024))) char smem[];   // K'[2] then V[2]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2;
     const int lq = lane & 31, lh = lane >> 5;
 
     // work decode: longest (last) query tiles first so that causal work drains evenly
@@ -173,192 +221,293 @@ __global__ __launch_bounds__(256, 1) void pasa_fwd(const _Float16* __restrict__ 
     const int hk = hq / (Hq / Hkv);
     const int ntile = N / T;
 
-    const int q0 = qt * ROWS_PER_WG;
-    const int qw0 = q0 + wave * ROWS_PER_WAVE;
-    const bool wave_valid = qw0 < N;       // N is a multiple of 128 and a wave owns 64 rows: all or nothing
-    int last_row_wg = q0 + ROWS_PER_WG - 1;
+    const int q0 = qt * RWG;
+    const int qw0 = q0 + wave * RW;
+    const bool wave_valid = qw0 < N;       // N is a multiple of 128 and a wave owns 32 rows: all or nothing
+    int last_row_wg = q0 + RWG - 1;
     if (last_row_wg > N - 1) last_row_wg = N - 1;
     const int J_wg = CAUSAL ? (last_row_wg / T + 1) : ntile;
-    const int J_w = wave_valid ? (CAUSAL ? ((qw0 + ROWS_PER_WAVE - 1) / T + 1) : ntile) : 0;
+    const int J_w = wave_valid ? (CAUSAL ? ((qw0 + RW - 1) / T + 1) : ntile) : 0;
+    const int row = qw0 + lq;
 
     const _Float16* qbase = q + ((size_t)(b * Hq + hq) * N) * D;
-    const _Float16* kbase = kp + ((size_t)(b * Hkv + hk) * ntile) * TILE_HALFS;
-    const _Float16* vbase = vt + ((size_t)(b * Hkv + hk) * ntile) * TILE_HALFS;
+    const char* wsbase = ws + ((size_t)(b * Hkv + hk) * ntile) * TILE_BYTES;
 
-    // Q fragments: B operand, lane (query lq of block qb, half lh) holds channels 16*ks + 8*lh .. +7
-    h8 Qf[2][KS];
-    if (wave_valid) {
+    auto issue_k = [&](int j) {
+        const char* src = wsbase + (size_t)j * TILE_BYTES;
+        char* dst = smem + (j & 1) * KT_BYTES;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int i = 0; i < CPW; ++i) copy_1k_to_lds(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
+    };
+    auto issue_v = [&](int j) {
+        const char* src = wsbase + (size_t)j * TILE_BYTES + KT_BYTES;
+        char* dst = smem + 2 * KT_BYTES + (j & 1) * KT_BYTES;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                Qf[qb][ks] = *reinterpret_cast<const h8*>(qbase + (size_t)(qw0 + 32 * qb + lq) * D + 16 * ks + 8 * lh);
-    } else {
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) Qf[qb][ks] = (h8)(_Float16)0;
-    }
+        for (int i = 0; i < CPW; ++i) copy_1k_to_lds(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
+    };
+    issue_k(0);
 
-    // per-row state (one query row per lane and query block; both halves of the wave hold copies)
-    float F[2], m[2], l[2];          // STRICT: values are always fp16-representable
-    f16v O[2][CB];                   // fp32 running output (not used by STRICT)
-    h2 O16[2][CB][8];                // fp16 running output (STRICT only)
+    // Q fragments: B operand, lane (query lq, half lh) holds channels 16*ks + 8*lh .. +7
+    h8 Qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        Qf[ks] = wave_valid ? *reinterpret_cast<const h8*>(qbase + (size_t)row * D + 16 * ks + 8 * lh) : (h8)(_Float16)0;
+
+    // per-row state (one query row per lane; both halves of the wave hold copies)
+    float F = 0.f, m = NAIVE ? -__builtin_inff() : 0.f, l = 0.f;   // STRICT: always fp16-representable values
+    float Lc = 0.f;                  // log of the scale of the stored output (fp32 variants)
+    float ec_s = 1.f, ep_s = 0.f;    // STRICT: factors of the pending output combination
+    f16v S[4];                       // S'^T accumulators
+    h8 Pf[8];                        // P^T, B operand of the second GEMM
+    f16v O[CB];                      // fp32 variants: stored output; STRICT: product of the latest tile
+    h2 O16[CB][8];                   // STRICT: running output
     unsigned long long n_ovf = 0;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        F[qb] = 0.f;
-        m[qb] = NAIVE ? -__builtin_inff() : 0.f;
-        l[qb] = 0.f;
+    for (int kb = 0; kb < 4; ++kb) S[kb] = (f16v)0.f;
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            O[qb][cb] = (f16v)0.f;
+    for (int kk = 0; kk < 8; ++kk) Pf[kk] = (h8)(_Float16)0;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) O16[qb][cb][t] = (h2)(_Float16)0;
-        }
+    for (int cb = 0; cb < CB; ++cb) {
+        O[cb] = (f16v)0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) O16[cb][t] = (h2)(_Float16)0;
     }
 
-    for (int j = 0; j < J_wg; ++j) {
-        __syncthreads();   // everyone is done with the previous tile
-        {
-            const h8* ks = reinterpret_cast<const h8*>(kbase + (size_t)j * TILE_HALFS);
-            const h8* vs = reinterpret_cast<const h8*>(vbase + (size_t)j * TILE_HALFS);
-            h8* kd = reinterpret_cast<h8*>(lds_k);
-            h8* vd = reinterpret_cast<h8*>(lds_v);
+    // STRICT: fold the product of tile jt (in O) into the running fp16 output
+    auto fold16 = [&](int jt) {
+        const _Float16 ec = (_Float16)ec_s, ep = (_Float16)ep_s;
+        const h2 ec2 = {ec, ec}, ep2 = {ep, ep};
 #pragma unroll
-            for (int i = 0; i < TILE_HALFS / 8 / 256; ++i) {
-                kd[tid + 256 * i] = ks[tid + 256 * i];
-                vd[tid + 256 * i] = vs[tid + 256 * i];
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const h2 ot = pack_rn(O[cb][2 * t], O[cb][2 * t + 1]);
+                if (jt == 0) {
+                    O16[cb][t] = ot;
+                } else {
+                    const h2 a1 = ec2 * ot;               // each packed op rounds to fp16 once
+                    const h2 a2 = ep2 * O16[cb][t];
+                    O16[cb][t] = a1 + a2;
+                }
+            }
+    };
+
+    // loads for the even global slot sg: K'(sg/2 + 1) and V(sg/2)
+    auto issue_slot = [&](int sg) {
+        const int jl = sg >> 1;
+        if (jl + 1 < J_wg) issue_k(jl + 1);
+        if (jl < J_wg) issue_v(jl);
+    };
+    auto drain_copies = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };   // vmcnt(0)
+
+    // Barrier b ends slot b-1 and starts slot b.  Group A runs M(j) in slot 2j and V(j) in slot 2j+1; group B runs
+    // M(j) in slot 2j+1 and V(j) in slot 2j+2.  Copies are issued at the start of every even slot by all waves and
+    // drained by their issuers before the barrier that starts the slot two later.
+    drain_copies();
+    __syncthreads();                       // barrier 0: K'(0) is in LDS
+    if (grp == 1) {
+        issue_slot(0);
+        __syncthreads();                   // barrier 1: group B idles through slot 0
+    }
+
+    for (int j = 0; j <= J_wg; ++j) {
+        if (grp == 0) issue_slot(2 * j);
+        // =========================== matrix part M(j) ===========================
+        if (j <= J_w) {
+            __builtin_amdgcn_s_setprio(1);
+        if (j >= 1 && j - 1 < J_w) {
+            // ---- second GEMM of tile j-1: (P V)^T, D channels x 32 queries ----
+            const _Float16* lds_v = reinterpret_cast<const _Float16*>(smem + 2 * KT_BYTES + ((j - 1) & 1) * KT_BYTES);
+            h8 a[PRE][CB];
+#pragma unroll
+            for (int pre = 0; pre < PRE; ++pre)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+                    a[pre][cb] = *reinterpret_cast<const h8*>(lds_v + ((2 * pre + lh) * D + 32 * cb + lq) * 8);
+            PASA_FENCE();
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    if (STRICT && kk == 0)
+                        O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kk % PRE][cb], Pf[kk], (f16v)0.f, 0, 0, 0);
+                    else
+                        O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kk % PRE][cb], Pf[kk], O[cb], 0, 0, 0);
+                }
+                PASA_FENCE();
+                if (kk + PRE < 8) {
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb)
+                        a[kk % PRE][cb] = *reinterpret_cast<const h8*>(lds_v + ((2 * (kk + PRE) + lh) * D + 32 * cb + lq) * 8);
+                    PASA_FENCE();
+                }
             }
         }
-        __syncthreads();
-        if (j >= J_w) continue;     // wave-uniform; the barriers above are still reached by every wave
-
-        // ---------------- first GEMM: S'^T tile (128 keys x 64 queries) ----------------
-        f16v S[2][4];
+        if (j < J_w) {
+            // ---- first GEMM of tile j: S'^T, 128 keys x 32 queries ----
+            const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (j & 1) * KT_BYTES);
+            h8 a[PRE][4];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+            for (int pre = 0; pre < PRE; ++pre)
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) S[qb][kb] = (f16v)0.f;
+                for (int kb = 0; kb < 4; ++kb)
+                    a[pre][kb] = *reinterpret_cast<const h8*>(lds_k + ((2 * pre + lh) * T + 32 * kb + lq) * 8);
+            PASA_FENCE();
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
+            for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-                const h8 a = *reinterpret_cast<const h8*>(lds_k + ((2 * ks + lh) * T + 32 * kb + lq) * 8);
-                S[0][kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Qf[0][ks], S[0][kb], 0, 0, 0);
-                S[1][kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Qf[1][ks], S[1][kb], 0, 0, 0);
+                for (int kb = 0; kb < 4; ++kb) {
+                    if (ks == 0)
+                        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks % PRE][kb], Qf[ks], (f16v)0.f, 0, 0, 0);
+                    else
+                        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks % PRE][kb], Qf[ks], S[kb], 0, 0, 0);
+                }
+                PASA_FENCE();
+                if (ks + PRE < KS) {
+#pragma unroll
+                    for (int kb = 0; kb < 4; ++kb)
+                        a[ks % PRE][kb] = *reinterpret_cast<const h8*>(lds_k + ((2 * (ks + PRE) + lh) * T + 32 * kb + lq) * 8);
+                    PASA_FENCE();
+                }
             }
+        }
+            __builtin_amdgcn_s_setprio(0);
+        }
+        if (grp == 1) drain_copies();
+        __syncthreads();
+        if (grp == 1) issue_slot(2 * j + 2);
+        if (j < J_w) {
+            const bool first = (j == 0);
+            if (STRICT && j >= 1) fold16(j - 1);
 
-        const bool diag = CAUSAL && (j * T + T - 1 > qw0);
-        h8 Pf[2][8];
-        float ec_[2], ep_[2];
-        bool first = (j == 0);
-
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int row = qw0 + 32 * qb + lq;
             // ---- S' as stored: fp32, or rounded to fp16 ----
             if (S16) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        const float s32 = S[qb][kb][i];
+                        const float s32 = S[kb][i];
                         if (INSTR) n_ovf += (__builtin_fabsf(s32) >= 65520.f) ? 1u : 0u;
-                        float s = (float)(_Float16)s32;
-                        if (NAIVE) s = s * scale;          // Eq. (2): static scaling after the GEMM
-                        S[qb][kb][i] = s;
+                        float sv = (float)(_Float16)s32;
+                        if (NAIVE) sv = sv * scale;          // Eq. (2): static scaling after the GEMM
+                        S[kb][i] = sv;
                     }
             } else if (INSTR) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) n_ovf += (__builtin_fabsf(S[qb][kb][i]) >= 65520.f) ? 1u : 0u;
+                    for (int i = 0; i < 16; ++i) n_ovf += (__builtin_fabsf(S[kb][i]) >= 65520.f) ? 1u : 0u;
             }
             // ---- pseudo-average over all 128 keys of the tile (before masking) ----
             float sbar = 0.f;
             if (!NAIVE) {
-                float sum = 0.f;
+                float ps[4];
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb)
+                for (int kb = 0; kb < 4; ++kb) {
+                    ps[kb] = S[kb][0];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) sum += S[qb][kb][i];
+                    for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
+                }
+                float sum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
                 sum += xor32(sum);
                 sbar = sum * (1.0f / T);
                 if (STRICT) sbar = (float)(_Float16)sbar;
             }
             // ---- causal mask (diagonal tiles only) ----
-            if (diag) {
+            if (CAUSAL && (j * T + T - 1 > qw0)) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = j * T + 32 * kb + 8 * (i >> 2) + 4 * lh + (i & 3);
-                        if (key > row) S[qb][kb][i] = -__builtin_inff();
+                        if (key > row) S[kb][i] = -__builtin_inff();
                     }
             }
             // ---- local maximum m' ----
-            float mx = -__builtin_inff();
+            float mx;
+            {
+                float pm[4];
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
+                for (int kb = 0; kb < 4; ++kb) {
+                    pm[kb] = S[kb][0];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = __builtin_fmaxf(mx, S[qb][kb][i]);
-            mx = __builtin_fmaxf(mx, xor32(mx));
-
+                    for (int i = 1; i < 16; ++i) pm[kb] = __builtin_fmaxf(pm[kb], S[kb][i]);
+                }
+                mx = __builtin_fmaxf(__builtin_fmaxf(pm[0], pm[1]), __builtin_fmaxf(pm[2], pm[3]));
+                mx = __builtin_fmaxf(mx, xor32(mx));
+            }
             // ---- reference level for exp: local m' (PASA), running max (plain FlashAttention) ----
             float mref = mx, e_old = 0.f;
             if (NAIVE) {
-                const float mnew = __builtin_fmaxf(m[qb], mx);
-                e_old = exp_nat(m[qb] - mnew);
-                m[qb] = mnew;
+                const float mnew = __builtin_fmaxf(m, mx);
+                e_old = exp_nat(m - mnew);
+                m = mnew;
                 mref = mnew;
             }
             // ---- P = exp(S' - m') rounded to fp16; l' = sum of the rounded P ----
-            float lsum = 0.f;
+            float lsum;
+            {
+                float pl[4];
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
+                for (int kb = 0; kb < 4; ++kb) {
+                    pl[kb] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float x = S[qb][kb][i] - mref;
-                    if (STRICT) x = (float)(_Float16)x;
-                    const _Float16 p = (_Float16)exp_nat(x);
-                    Pf[qb][2 * kb + (i >> 3)][i & 7] = p;
-                    lsum += (float)p;
+                    for (int t2 = 0; t2 < 8; ++t2) {
+                        float x0 = S[kb][2 * t2] - mref, x1 = S[kb][2 * t2 + 1] - mref;
+                        if (STRICT) {
+                            x0 = (float)(_Float16)x0;
+                            x1 = (float)(_Float16)x1;
+                        }
+                        const h2 p2 = pack_rn(exp_nat(x0), exp_nat(x1));
+                        Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3)] = p2[0];
+                        Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
+                        pl[kb] = add_pair(p2, pl[kb]);
+                    }
                 }
-            lsum += xor32(lsum);
-            if (STRICT) lsum = (float)(_Float16)lsum;
+                lsum = (pl[0] + pl[1]) + (pl[2] + pl[3]);
+                lsum += xor32(lsum);
+                if (STRICT) lsum = (float)(_Float16)lsum;
+            }
 
-            // ---- global recovering (step 3) and the running sum (step 4) ----
+            // ---- global recovering (step 3), the running sum (step 4) and the output rescale factor ----
+            float g = 0.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
+            bool drop = false;    // this row's tile j is too far below the running maximum to matter
             if (NAIVE) {
-                l[qb] = e_old * l[qb] + lsum;
-                ep_[qb] = e_old;
-                ec_[qb] = 1.f;
+                l = e_old * l + lsum;
+                g = e_old;
             } else if (first) {
-                F[qb] = sbar;
-                m[qb] = mx;
-                l[qb] = lsum;
-                ep_[qb] = 0.f;
-                ec_[qb] = 1.f;
+                F = sbar;
+                m = mx;
+                l = lsum;
+                Lc = 0.f;
+                ec_s = 1.f;
+                ep_s = 0.f;
             } else if (!STRICT) {
-                const float jm1 = (float)j, jj = (float)(j + 1);
-                const float Fn = (jm1 * F[qb] + sbar) / jj;
-                const float dpp = inva * (F[qb] - Fn);
+                const float jm1 = (float)j, jn = (float)(j + 1);
+                const float Fn = (jm1 * F + sbar) / jn;
+                const float dpp = inva * (F - Fn);
                 const float dpc = inva * (sbar - Fn);
-                const float mn = __builtin_fmaxf(m[qb] + dpp, mx + dpc);
-                const float dp = (m[qb] - mn) + dpp;
+                const float mn = __builtin_fmaxf(m + dpp, mx + dpc);
+                const float dp = (m - mn) + dpp;
                 const float dc = (mx - mn) + dpc;
                 const float ep = exp_nat(dp), ec = exp_nat(dc);
-                l[qb] = ep * l[qb] + ec * lsum;
-                F[qb] = Fn;
-                m[qb] = mn;
-                ep_[qb] = ep;
-                ec_[qb] = ec;
+                l = ep * l + ec * lsum;
+                F = Fn;
+                m = mn;
+                drop = dc < -60.f;
+                if (drop) {
+                    Lc = dp + Lc;             // O_j = e^{dp} O_{j-1}: same stored output, smaller scale
+                    g = 1.f;
+                } else {
+                    g = exp_nat((dp + Lc) - dc);
+                    Lc = dc;
+                }
             } else {
                 // every operation rounded to fp16, in the order Algorithm 1 states them
-                const _Float16 jm1 = (_Float16)(float)j, jj = (_Float16)(float)(j + 1);
-                const _Float16 Fo = (_Float16)F[qb], sb = (_Float16)sbar, mo = (_Float16)m[qb], mxh = (_Float16)mx;
+                const _Float16 jm1 = (_Float16)(float)j, jn = (_Float16)(float)(j + 1);
+                const _Float16 Fo = (_Float16)F, sb = (_Float16)sbar, mo = (_Float16)m, mxh = (_Float16)mx;
                 const _Float16 iv = (_Float16)inva;
-                const _Float16 Fn = (_Float16)((_Float16)((_Float16)(jm1 * Fo) + sb) / jj);
+                const _Float16 Fn = (_Float16)((_Float16)((_Float16)(jm1 * Fo) + sb) / jn);
                 const _Float16 dpp = (_Float16)(iv * (_Float16)(Fo - Fn));
                 const _Float16 dpc = (_Float16)(iv * (_Float16)(sb - Fn));
                 const _Float16 c1 = (_Float16)(mo + dpp), c2 = (_Float16)(mxh + dpc);
@@ -366,94 +515,60 @@ __global__ __launch_bounds__(256, 1) void pasa_fwd(const _Float16* __restrict__ 
                 const _Float16 dp = (_Float16)((_Float16)(mo - mn) + dpp);
                 const _Float16 dc = (_Float16)((_Float16)(mxh - mn) + dpc);
                 const _Float16 ep = (_Float16)exp_nat((float)dp), ec = (_Float16)exp_nat((float)dc);
-                const _Float16 lo = (_Float16)l[qb], ln = (_Float16)lsum;
-                l[qb] = (float)(_Float16)((_Float16)(ep * lo) + (_Float16)(ec * ln));
-                F[qb] = (float)Fn;
-                m[qb] = (float)mn;
-                ep_[qb] = (float)ep;
-                ec_[qb] = (float)ec;
+                const _Float16 lo = (_Float16)l, ln = (_Float16)lsum;
+                l = (float)(_Float16)((_Float16)(ep * lo) + (_Float16)(ec * ln));
+                F = (float)Fn;
+                m = (float)mn;
+                ep_s = (float)ep;
+                ec_s = (float)ec;
             }
-        }
-
-        // ---------------- second GEMM: (P V)^T tile (D channels x 64 queries) ----------------
-        f16v Ot[2][CB];
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) Ot[qb][cb] = (f16v)0.f;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb) {
-                const h8 a = *reinterpret_cast<const h8*>(lds_v + ((2 * kk + lh) * D + 32 * cb + lq) * 8);
-                Ot[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Pf[0][kk], Ot[0][cb], 0, 0, 0);
-                Ot[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, Pf[1][kk], Ot[1][cb], 0, 0, 0);
-            }
-
-        // ---------------- corrected output update (step 4) ----------------
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
             if (!STRICT) {
-                const float ec = ec_[qb], ep = ep_[qb];
-                if (first) {
+                if (__builtin_amdgcn_ballot_w64(drop) != 0ull) {
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) O[qb][cb] = Ot[qb][cb];
-                } else {
+                    for (int kk = 0; kk < 8; ++kk)
+                        if (drop) Pf[kk] = (h8)(_Float16)0;
+                }
+                if (!first) {
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) O[qb][cb][i] = ec * Ot[qb][cb][i] + ep * O[qb][cb][i];
+                        for (int i = 0; i < 16; ++i) O[cb][i] *= g;
                 }
-            } else {
-                const _Float16 ec = (_Float16)ec_[qb], ep = (_Float16)ep_[qb];
-                const h2 ec2 = {ec, ec}, ep2 = {ep, ep};
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        const h2 ot = {(_Float16)Ot[qb][cb][2 * t], (_Float16)Ot[qb][cb][2 * t + 1]};
-                        if (first) {
-                            O16[qb][cb][t] = ot;
-                        } else {
-                            const h2 a1 = ec2 * ot;               // each packed op rounds to fp16 once
-                            const h2 a2 = ep2 * O16[qb][cb][t];
-                            O16[qb][cb][t] = a1 + a2;
-                        }
-                    }
             }
         }
+        if (grp == 0) drain_copies();
+        __syncthreads();
     }
+    if (grp == 0) __syncthreads();         // group B's last barrier
 
     // ---------------- final normalisation and store ----------------
     unsigned long long n_bad = 0;
     if (wave_valid) {
+        if (STRICT) fold16(J_w - 1);
+        const float oscale = STRICT ? 0.f : exp_nat(Lc) / l;
         _Float16* obase = o + ((size_t)(b * Hq + hq) * N) * D;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            const int row = qw0 + 32 * qb + lq;
+        for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
+            for (int gq = 0; gq < 4; ++gq) {
+                h4 out;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    h4 out;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int i = 4 * g + r;
-                        _Float16 val;
-                        if (!STRICT) {
-                            val = (_Float16)(O[qb][cb][i] / l[qb]);
-                        } else {
-                            val = (_Float16)(O16[qb][cb][i >> 1][i & 1] / (_Float16)l[qb]);
-                        }
-                        if (INSTR) {
-                            const float fv = (float)val;
-                            n_bad += (fv != fv || __builtin_fabsf(fv) == __builtin_inff()) ? 1u : 0u;
-                        }
-                        out[r] = val;
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 4 * gq + r;
+                    _Float16 val;
+                    if (!STRICT) {
+                        val = (_Float16)(O[cb][i] * oscale);
+                    } else {
+                        val = (_Float16)(O16[cb][i >> 1][i & 1] / (_Float16)l);
                     }
-                    *reinterpret_cast<h4*>(obase + (size_t)row * D + 32 * cb + 8 * g + 4 * lh) = out;
+                    if (INSTR) {
+                        const float fv = (float)val;
+                        n_bad += (fv != fv || __builtin_fabsf(fv) == __builtin_inff()) ? 1u : 0u;
+                    }
+                    out[r] = val;
                 }
-        }
+                *reinterpret_cast<h4*>(obase + (size_t)row * D + 32 * cb + 8 * gq + 4 * lh) = out;
+            }
     }
     if (INSTR) {
         if (ovf_s != nullptr && n_ovf) atomicAdd(ovf_s, n_ovf);
@@ -464,11 +579,16 @@ __global__ __launch_bounds__(256, 1) void pasa_fwd(const _Float16* __restrict__ 
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 hipError_t launch_fwd(const PasaLaunch& p)
 {
-    const int nqt = (p.N + ROWS_PER_WG - 1) / ROWS_PER_WG;
+    constexpr int RWG = 256;
+    constexpr int LDS_BYTES = 4 * (T * D * 2);
+    const int nqt = (p.N + RWG - 1) / RWG;
     const dim3 grid((unsigned)(nqt * p.Hq * p.B));
-    hipLaunchKernelGGL((pasa_fwd<D, VAR, CAUSAL, INSTR>), grid, dim3(256), 0, p.stream,
-                       (const _Float16*)p.q, (const _Float16*)p.kp, (const _Float16*)p.vt, (_Float16*)p.o,
-                       p.Hq, p.Hkv, p.N, nqt, p.inva, p.scale, p.overflow_s, p.nonfinite_o);
+    auto kern = pasa_fwd<D, VAR, CAUSAL, INSTR>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       LDS_BYTES);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
+                       (_Float16*)p.o, p.Hq, p.Hkv, p.N, nqt, p.inva, p.scale, p.overflow_s, p.nonfinite_o);
     return hipGetLastError();
 }
 
@@ -494,16 +614,16 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 
 }  // namespace
 
-hipError_t pasa_launch_prep(const void* k, const void* v, void* kp, void* vt, void* plain_out,
+hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, hipStream_t stream)
 {
     const dim3 grid((unsigned)((size_t)B * Hkv * (N / T)));
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)kp, (_Float16*)vt, (_Float16*)plain_out, beta, kscale);
+                           (_Float16*)ws, (_Float16*)plain_out, beta, kscale);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)kp, (_Float16*)vt, (_Float16*)plain_out, beta, kscale);
+                           (_Float16*)ws, (_Float16*)plain_out, beta, kscale);
     return hipGetLastError();
 }
 
