@@ -27,6 +27,7 @@
 // Algorithm 1 marks them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "pasa_kernels.h"
 
@@ -141,7 +142,29 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
 // ---------------------------------------------------------------------------------------------
 // Main kernel
 // ---------------------------------------------------------------------------------------------
-__device__ inline float xor32(float x) { return __shfl_xor(x, 32, 64); }
+// Value of x in the lane 32 away (lane l <-> lane l^32), without going through the LDS crossbar: the LDS pipe is
+// saturated by the other wave group's fragment reads while this is needed.  v_permlane32_swap exchanges lanes 32-63
+// of its first operand with lanes 0-31 of its second; with two copies of x that leaves [x_lo, x_lo] and [x_hi, x_hi].
+// The s_nop cover the VALU-write -> permlane-read and permlane-write -> VALU-read wait states, which the compiler
+// cannot see through inline assembly.
+__device__ inline void halves32(float x, float& lo, float& hi)
+{
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+}
+__device__ inline float sum32(float x)
+{
+    float lo, hi;
+    halves32(x, lo, hi);
+    return lo + hi;
+}
+__device__ inline float max32(float x)
+{
+    float lo, hi;
+    halves32(x, lo, hi);
+    return __builtin_fmaxf(lo, hi);
+}
 
 __device__ inline float exp_nat(float x) { return __builtin_amdgcn_exp2f(x * LOG2E); }
 
@@ -160,16 +183,31 @@ __device__ inline float add_pair(h2 v, float acc)
 
 // One wave-wide direct global -> LDS copy of 1 KiB: lane i moves 16 bytes from gsrc + 16*i to ldst + 16*i.
 // ldst must be wave-uniform (it travels in M0).
+// OFF is an immediate added to both addresses, so a wave's consecutive pieces share one M0 value.
+template <int OFF>
 __device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
 {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc + lane * 16),
-                                     (__attribute__((address_space(3))) void*)ldst, 16, 0, 0);
+                                     (__attribute__((address_space(3))) void*)ldst, 16, OFF, 0);
 }
 
 #define PASA_FENCE() __builtin_amdgcn_sched_barrier(0)
 #ifndef PASA_PRE
-#define PASA_PRE 1
+#define PASA_PRE 2
 #endif
+#ifndef PASA_MPRIO
+#define PASA_MPRIO 1
+#endif
+#ifndef PASA_VPRIO
+#define PASA_VPRIO 0
+#endif
+#ifndef PASA_GRP
+#define PASA_GRP(w) ((w) >> 2)
+#endif
+#ifndef PASA_ABL
+#define PASA_ABL 0
+#endif
+#define ABL_LD(p) ((PASA_ABL & 4) ? Qf[0] : *reinterpret_cast<const h8*>(p))
 
 // A workgroup is 8 wavefronts and owns 256 query rows, 32 per wavefront.  Wavefronts 0-3 (group A) and 4-7
 // (group B) sit pairwise on the four SIMDs and run the same program half a tile apart: time is cut into slots
@@ -204,19 +242,21 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     constexpr int TILE_BYTES = 2 * KT_BYTES;                    // workspace stride: K' tile then V tile
     constexpr int CPW = KT_BYTES / 1024 / 8;                    // 1 KiB copies per wave per K' (or V) tile
     constexpr int RW = 32, RWG = 256;
-    constexpr int PRE = PASA_PRE;                               // k-steps of LDS fragments in flight
+    constexpr int PRE = (STRICT && D == 128) ? 1 : PASA_PRE;   // k-steps of LDS fragments in flight (register budget)
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];   // K'[2] then V[2]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = wave >> 2;
+    const int grp = PASA_GRP(wave);
     const int lq = lane & 31, lh = lane >> 5;
 
-    // work decode: longest (last) query tiles first so that causal work drains evenly
+    // work decode: workgroups are dispatched in index order, so the query tiles with the most key tiles (the last
+    // ones when causal) come first for every head: longest-processing-time-first keeps the tail short
     const int wg = blockIdx.x;
-    const int qt = nqt - 1 - (wg % nqt);
-    const int bh = wg / nqt;
+    const int nbh = gridDim.x / nqt;
+    const int qt = nqt - 1 - wg / nbh;
+    const int bh = wg % nbh;
     const int hq = bh % Hq, b = bh / Hq;
     const int hk = hq / (Hq / Hkv);
     const int ntile = N / T;
@@ -237,13 +277,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         const char* src = wsbase + (size_t)j * TILE_BYTES;
         char* dst = smem + (j & 1) * KT_BYTES;
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) copy_1k_to_lds(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
+        for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
     };
     auto issue_v = [&](int j) {
         const char* src = wsbase + (size_t)j * TILE_BYTES + KT_BYTES;
         char* dst = smem + 2 * KT_BYTES + (j & 1) * KT_BYTES;
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) copy_1k_to_lds(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
+        for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
     };
     issue_k(0);
 
@@ -292,11 +332,39 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
     };
 
-    // loads for the even global slot sg: K'(sg/2 + 1) and V(sg/2)
-    auto issue_slot = [&](int sg) {
+    // The copies of the even global slot sg are K'(sg/2 + 1) and V(sg/2); each wave owns 2*CPW of their 1 KiB pieces.
+    // They are issued one at a time, spread over the slot, because a burst of 64 wave-wide copies fills the address
+    // FIFO of the texture path and stalls the issuing waves for hundreds of cycles.
+    auto issue_piece = [&](int sg, auto piece_c) {
+        constexpr int piece = decltype(piece_c)::value;       // 0 .. 2*CPW-1: K' pieces first, then V pieces
         const int jl = sg >> 1;
-        if (jl + 1 < J_wg) issue_k(jl + 1);
-        if (jl < J_wg) issue_v(jl);
+        if (piece < CPW) {
+            if (jl + 1 < J_wg)
+                copy_1k_to_lds<(piece % CPW) * 1024>(wsbase + (size_t)(jl + 1) * TILE_BYTES + wave * (CPW * 1024),
+                                                     smem + ((jl + 1) & 1) * KT_BYTES + wave * (CPW * 1024), lane);
+        } else {
+            if (jl < J_wg)
+                copy_1k_to_lds<(piece % CPW) * 1024>(wsbase + (size_t)jl * TILE_BYTES + KT_BYTES + wave * (CPW * 1024),
+                                                     smem + 2 * KT_BYTES + (jl & 1) * KT_BYTES + wave * (CPW * 1024), lane);
+        }
+    };
+    // idx is a constant after unrolling; the switch turns it back into a template argument (an instruction immediate)
+    auto issue_copy = [&](int sg, int idx) {
+        switch (idx) {
+            case 0: issue_piece(sg, std::integral_constant<int, 0>{}); break;
+            case 1: issue_piece(sg, std::integral_constant<int, 1>{}); break;
+            case 2: issue_piece(sg, std::integral_constant<int, 2 % (2 * CPW)>{}); break;
+            case 3: issue_piece(sg, std::integral_constant<int, 3 % (2 * CPW)>{}); break;
+            case 4: issue_piece(sg, std::integral_constant<int, 4 % (2 * CPW)>{}); break;
+            case 5: issue_piece(sg, std::integral_constant<int, 5 % (2 * CPW)>{}); break;
+            case 6: issue_piece(sg, std::integral_constant<int, 6 % (2 * CPW)>{}); break;
+            case 7: issue_piece(sg, std::integral_constant<int, 7 % (2 * CPW)>{}); break;
+            default: break;
+        }
+    };
+    auto issue_slot = [&](int sg) {
+#pragma unroll
+        for (int idx = 0; idx < 2 * CPW; ++idx) issue_copy(sg, idx);
     };
     auto drain_copies = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };   // vmcnt(0)
 
@@ -310,12 +378,24 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         __syncthreads();                   // barrier 1: group B idles through slot 0
     }
 
+    long long tM = 0, tV = 0, tB = 0, t0 = 0, t1 = 0;
     for (int j = 0; j <= J_wg; ++j) {
-        if (grp == 0) issue_slot(2 * j);
+        if (PASA_ABL & 16) t0 = __builtin_readcyclecounter();
         // =========================== matrix part M(j) ===========================
+        const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
+        if (grp == 0) {   // group A spreads its copies over the GEMM steps; whatever has no GEMM to hide behind goes now
+            if (!do_g2) {
+#pragma unroll
+                for (int idx = 0; idx < CPW; ++idx) issue_copy(2 * j, idx);
+            }
+            if (!do_g1) {
+#pragma unroll
+                for (int idx = CPW; idx < 2 * CPW; ++idx) issue_copy(2 * j, idx);
+            }
+        }
         if (j <= J_w) {
-            __builtin_amdgcn_s_setprio(1);
-        if (j >= 1 && j - 1 < J_w) {
+            __builtin_amdgcn_s_setprio(PASA_MPRIO);
+        if (do_g2) {
             // ---- second GEMM of tile j-1: (P V)^T, D channels x 32 queries ----
             const _Float16* lds_v = reinterpret_cast<const _Float16*>(smem + 2 * KT_BYTES + ((j - 1) & 1) * KT_BYTES);
             h8 a[PRE][CB];
@@ -323,13 +403,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             for (int pre = 0; pre < PRE; ++pre)
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
-                    a[pre][cb] = *reinterpret_cast<const h8*>(lds_v + ((2 * pre + lh) * D + 32 * cb + lq) * 8);
+                    a[pre][cb] = ABL_LD(lds_v + ((2 * pre + lh) * D + 32 * cb + lq) * 8);
             PASA_FENCE();
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
+            for (int kk = 0; kk < ((PASA_ABL & 8) ? 1 : 8); ++kk) {
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb) {
-                    if (STRICT && kk == 0)
+                    if (PASA_ABL & 2)
+                        asm volatile("" ::"v"(a[kk % PRE][cb]));
+                    else if (STRICT && kk == 0)
                         O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kk % PRE][cb], Pf[kk], (f16v)0.f, 0, 0, 0);
                     else
                         O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kk % PRE][cb], Pf[kk], O[cb], 0, 0, 0);
@@ -338,12 +420,16 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 if (kk + PRE < 8) {
 #pragma unroll
                     for (int cb = 0; cb < CB; ++cb)
-                        a[kk % PRE][cb] = *reinterpret_cast<const h8*>(lds_v + ((2 * (kk + PRE) + lh) * D + 32 * cb + lq) * 8);
+                        a[kk % PRE][cb] = ABL_LD(lds_v + ((2 * (kk + PRE) + lh) * D + 32 * cb + lq) * 8);
+                    PASA_FENCE();
+                }
+                if (grp == 0 && (kk % (8 / CPW)) == 8 / CPW - 1) {
+                    issue_copy(2 * j, kk / (8 / CPW));
                     PASA_FENCE();
                 }
             }
         }
-        if (j < J_w) {
+        if (do_g1) {
             // ---- first GEMM of tile j: S'^T, 128 keys x 32 queries ----
             const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (j & 1) * KT_BYTES);
             h8 a[PRE][4];
@@ -351,13 +437,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             for (int pre = 0; pre < PRE; ++pre)
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
-                    a[pre][kb] = *reinterpret_cast<const h8*>(lds_k + ((2 * pre + lh) * T + 32 * kb + lq) * 8);
+                    a[pre][kb] = ABL_LD(lds_k + ((2 * pre + lh) * T + 32 * kb + lq) * 8);
             PASA_FENCE();
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+            for (int ks = 0; ks < ((PASA_ABL & 8) ? 1 : KS); ++ks) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
-                    if (ks == 0)
+                    if (PASA_ABL & 2)
+                        asm volatile("" ::"v"(a[ks % PRE][kb]));
+                    else if (ks == 0)
                         S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks % PRE][kb], Qf[ks], (f16v)0.f, 0, 0, 0);
                     else
                         S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks % PRE][kb], Qf[ks], S[kb], 0, 0, 0);
@@ -366,17 +454,23 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 if (ks + PRE < KS) {
 #pragma unroll
                     for (int kb = 0; kb < 4; ++kb)
-                        a[ks % PRE][kb] = *reinterpret_cast<const h8*>(lds_k + ((2 * (ks + PRE) + lh) * T + 32 * kb + lq) * 8);
+                        a[ks % PRE][kb] = ABL_LD(lds_k + ((2 * (ks + PRE) + lh) * T + 32 * kb + lq) * 8);
+                    PASA_FENCE();
+                }
+                if (grp == 0 && (ks % (KS / CPW)) == KS / CPW - 1) {
+                    issue_copy(2 * j, CPW + ks / (KS / CPW));
                     PASA_FENCE();
                 }
             }
         }
-            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_s_setprio(PASA_VPRIO);
         }
+        if (PASA_ABL & 16) { t1 = __builtin_readcyclecounter(); tM += t1 - t0; }
         if (grp == 1) drain_copies();
         __syncthreads();
-        if (grp == 1) issue_slot(2 * j + 2);
-        if (j < J_w) {
+        if (PASA_ABL & 16) { t0 = __builtin_readcyclecounter(); tB += t0 - t1; }
+        if (grp == 1 && !(j < J_w && !(PASA_ABL & 1))) issue_slot(2 * j + 2);   // no vector part to spread them over
+        if (j < J_w && !(PASA_ABL & 1)) {
             const bool first = (j == 0);
             if (STRICT && j >= 1) fold16(j - 1);
 
@@ -409,7 +503,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
                 }
                 float sum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
-                sum += xor32(sum);
+                sum = sum32(sum);
                 sbar = sum * (1.0f / T);
                 if (STRICT) sbar = (float)(_Float16)sbar;
             }
@@ -434,7 +528,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     for (int i = 1; i < 16; ++i) pm[kb] = __builtin_fmaxf(pm[kb], S[kb][i]);
                 }
                 mx = __builtin_fmaxf(__builtin_fmaxf(pm[0], pm[1]), __builtin_fmaxf(pm[2], pm[3]));
-                mx = __builtin_fmaxf(mx, xor32(mx));
+                mx = max32(mx);
             }
             // ---- reference level for exp: local m' (PASA), running max (plain FlashAttention) ----
             float mref = mx, e_old = 0.f;
@@ -447,25 +541,35 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             // ---- P = exp(S' - m') rounded to fp16; l' = sum of the rounded P ----
             float lsum;
             {
+                const float nml = -mref * LOG2E;
                 float pl[4];
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
                     pl[kb] = 0.f;
 #pragma unroll
                     for (int t2 = 0; t2 < 8; ++t2) {
-                        float x0 = S[kb][2 * t2] - mref, x1 = S[kb][2 * t2 + 1] - mref;
-                        if (STRICT) {
-                            x0 = (float)(_Float16)x0;
-                            x1 = (float)(_Float16)x1;
+                        float e0, e1;
+                        if (STRICT) {   // the difference is itself rounded to fp16 before the exponential
+                            e0 = exp_nat((float)(_Float16)(S[kb][2 * t2] - mref));
+                            e1 = exp_nat((float)(_Float16)(S[kb][2 * t2 + 1] - mref));
+                        } else {        // exp(s - m) = 2^(s*log2e - m*log2e), one fused multiply-add per element
+                            e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][2 * t2], LOG2E, nml));
+                            e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][2 * t2 + 1], LOG2E, nml));
                         }
-                        const h2 p2 = pack_rn(exp_nat(x0), exp_nat(x1));
+                        const h2 p2 = pack_rn(e0, e1);
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3)] = p2[0];
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
                         pl[kb] = add_pair(p2, pl[kb]);
                     }
+                    if (grp == 1) {   // group B spreads its copies over the exponentials
+                        PASA_FENCE();
+#pragma unroll
+                        for (int idx = kb * (2 * CPW) / 4; idx < (kb + 1) * (2 * CPW) / 4; ++idx) issue_copy(2 * j + 2, idx);
+                        PASA_FENCE();
+                    }
                 }
                 lsum = (pl[0] + pl[1]) + (pl[2] + pl[3]);
-                lsum += xor32(lsum);
+                lsum = sum32(lsum);
                 if (STRICT) lsum = (float)(_Float16)lsum;
             }
 
@@ -536,10 +640,17 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 }
             }
         }
+        if (PASA_ABL & 16) { t1 = __builtin_readcyclecounter(); tV += t1 - t0; }
         if (grp == 0) drain_copies();
         __syncthreads();
+        if (PASA_ABL & 16) { tB += __builtin_readcyclecounter() - t1; }
     }
     if (grp == 0) __syncthreads();         // group B's last barrier
+    if ((PASA_ABL & 16) && blockIdx.x == 0 && lane == 0 && nonfinite_o != nullptr) {
+        nonfinite_o[wave * 3 + 0] = tM;
+        nonfinite_o[wave * 3 + 1] = tV;
+        nonfinite_o[wave * 3 + 2] = tB;
+    }
 
     // ---------------- final normalisation and store ----------------
     unsigned long long n_bad = 0;
@@ -595,7 +706,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
 template <int D, int VAR>
 hipError_t launch_fwd_cv(const PasaLaunch& p)
 {
-    const bool instr = p.overflow_s != nullptr || p.nonfinite_o != nullptr;
+    const bool instr = !(PASA_ABL & 16) && (p.overflow_s != nullptr || p.nonfinite_o != nullptr);
     if (p.causal) return instr ? launch_fwd<D, VAR, true, true>(p) : launch_fwd<D, VAR, true, false>(p);
     return instr ? launch_fwd<D, VAR, false, true>(p) : launch_fwd<D, VAR, false, false>(p);
 }
