@@ -192,9 +192,6 @@ __device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
 }
 
 #define PASA_FENCE() __builtin_amdgcn_sched_barrier(0)
-#ifndef PASA_PRE
-#define PASA_PRE 2
-#endif
 #ifndef PASA_MPRIO
 #define PASA_MPRIO 1
 #endif
@@ -242,7 +239,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     constexpr int TILE_BYTES = 2 * KT_BYTES;                    // workspace stride: K' tile then V tile
     constexpr int CPW = KT_BYTES / 1024 / 8;                    // 1 KiB copies per wave per K' (or V) tile
     constexpr int RW = 32, RWG = 256;
-    constexpr int PRE = (STRICT && D == 128) ? 1 : PASA_PRE;   // k-steps of LDS fragments in flight (register budget)
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];   // K'[2] then V[2]
 
@@ -251,14 +247,35 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     const int grp = PASA_GRP(wave);
     const int lq = lane & 31, lh = lane >> 5;
 
-    // work decode: workgroups are dispatched in index order, so the query tiles with the most key tiles (the last
-    // ones when causal) come first for every head: longest-processing-time-first keeps the tail short
+    // Work decode.  Workgroups are dispatched in index order and dealt round-robin to the 8 XCDs (index % 8), each
+    // with its own L2.  Two goals: (1) every XCD walks its share longest-first -- the query tiles with the most key
+    // tiles (the last ones when causal) first -- which keeps the tail of the launch short; (2) the query heads that
+    // share one KV head run on the same XCD(s), so that K'/V tiles are fetched into as few L2s as possible.
+    // A "group" is the set of Hq/Hkv query heads of one (batch, KV head).
     const int wg = blockIdx.x;
-    const int nbh = gridDim.x / nqt;
-    const int qt = nqt - 1 - wg / nbh;
-    const int bh = wg % nbh;
-    const int hq = bh % Hq, b = bh / Hq;
-    const int hk = hq / (Hq / Hkv);
+    const int G = Hq / Hkv;                 // query heads per group
+    const int ngroups = gridDim.x / (nqt * G);
+    int qt, grp_id, hin;                    // query tile, group, head within group
+    if (ngroups % 8 == 0) {                 // each XCD owns ngroups/8 whole groups
+        const int x = wg & 7, r = wg >> 3, per = (ngroups >> 3) * G;
+        qt = nqt - 1 - r / per;
+        grp_id = x + 8 * ((r % per) / G);
+        hin = (r % per) % G;
+    } else if (8 % ngroups == 0 && (nqt * G) % (8 / ngroups) == 0) {   // each group is spread over 8/ngroups XCDs
+        const int span = 8 / ngroups, x = wg & 7, r = wg >> 3;
+        const int i = r * span + (x % span);
+        grp_id = x / span;
+        qt = nqt - 1 - i / G;
+        hin = i % G;
+    } else {                                // plain longest-first order
+        const int nbh = ngroups * G;
+        qt = nqt - 1 - wg / nbh;
+        grp_id = (wg % nbh) / G;
+        hin = (wg % nbh) % G;
+    }
+    const int b = grp_id / Hkv, hk_ = grp_id % Hkv;
+    const int hq = hk_ * G + hin;
+    const int hk = hk_;
     const int ntile = N / T;
 
     const int q0 = qt * RWG;
@@ -276,12 +293,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     auto issue_k = [&](int j) {
         const char* src = wsbase + (size_t)j * TILE_BYTES;
         char* dst = smem + (j & 1) * KT_BYTES;
-#pragma unroll
-        for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
-    };
-    auto issue_v = [&](int j) {
-        const char* src = wsbase + (size_t)j * TILE_BYTES + KT_BYTES;
-        char* dst = smem + 2 * KT_BYTES + (j & 1) * KT_BYTES;
 #pragma unroll
         for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
     };
@@ -378,11 +389,76 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         __syncthreads();                   // barrier 1: group B idles through slot 0
     }
 
+    // Hand-offs between the parts of one wave.
+    float g_pend = 1.f;              // fp32 variants: factor for the stored output before the pending product is added
+    float ps[4], pm[4];              // partial row sums / maxima of S'(j) taken under the second GEMM (EARLY)
+    bool stats_ready = false;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) ps[kb] = pm[kb] = 0.f;
+    // MIXED takes the two row reductions of S'(j) while the second GEMM of tile j-1 runs (same wave, co-issued with
+    // its MFMAs) and applies the output rescale under the first GEMM, which shortens the vector part.
+    constexpr bool EARLY = (VAR == PASA_K_MIXED) && !INSTR;
+
+    // Both GEMMs run as one chain of MFMAs per accumulator block (the block index is the slow one), with the LDS
+    // fragments PF instructions ahead.  hook(n) is vector work of the same wave placed behind MFMA n; it is issued
+    // while that MFMA executes.
+    constexpr int PF = 4;
+    constexpr int NM1 = 4 * KS;      // MFMAs of the first GEMM:  n = kb * KS + ks
+    constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM: n = cb * 8 + kk
+    auto gemm1 = [&](int jt, auto&& hook) {   // S'^T of tile jt: 128 keys x 32 queries
+        const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (jt & 1) * KT_BYTES);
+        auto frag = [&](int n) { return ABL_LD(lds_k + ((2 * (n % KS) + lh) * T + 32 * (n / KS) + lq) * 8); };
+        h8 a[PF];
+#pragma unroll
+        for (int n = 0; n < PF; ++n) a[n] = frag(n);
+        PASA_FENCE();
+#pragma unroll
+        for (int n = 0; n < NM1; ++n) {
+            const int kb = n / KS, ks = n % KS;
+            if (PASA_ABL & 2)
+                asm volatile("" ::"v"(a[n % PF]));
+            else if (ks == 0)
+                S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], (f16v)0.f, 0, 0, 0);
+            else
+                S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], S[kb], 0, 0, 0);
+            PASA_FENCE();
+            hook(n);
+            if (n + PF < NM1) a[n % PF] = frag(n + PF);
+            if (grp == 0 && (n % (NM1 / CPW)) == NM1 / CPW - 1) issue_copy(2 * jt, CPW + n / (NM1 / CPW));
+            PASA_FENCE();
+        }
+    };
+    auto gemm2 = [&](int jt, auto&& hook) {   // (P V)^T of tile jt: D channels x 32 queries; runs during M(jt+1)
+        const _Float16* lds_v = reinterpret_cast<const _Float16*>(smem + 2 * KT_BYTES + (jt & 1) * KT_BYTES);
+        auto frag = [&](int n) { return ABL_LD(lds_v + ((2 * (n % 8) + lh) * D + 32 * (n / 8) + lq) * 8); };
+        h8 a[PF];
+#pragma unroll
+        for (int n = 0; n < PF; ++n) a[n] = frag(n);
+        PASA_FENCE();
+#pragma unroll
+        for (int n = 0; n < NM2; ++n) {
+            const int cb = n / 8, kk = n % 8;
+            if (PASA_ABL & 2)
+                asm volatile("" ::"v"(a[n % PF]));
+            else if (STRICT && kk == 0)
+                O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Pf[kk], (f16v)0.f, 0, 0, 0);
+            else
+                O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Pf[kk], O[cb], 0, 0, 0);
+            PASA_FENCE();
+            hook(n);
+            if (n + PF < NM2) a[n % PF] = frag(n + PF);
+            if (grp == 0 && (n % (NM2 / CPW)) == NM2 / CPW - 1) issue_copy(2 * (jt + 1), n / (NM2 / CPW));
+            PASA_FENCE();
+        }
+    };
+    auto no_hook = [](int) {};
+
     long long tM = 0, tV = 0, tB = 0, t0 = 0, t1 = 0;
     for (int j = 0; j <= J_wg; ++j) {
         if (PASA_ABL & 16) t0 = __builtin_readcyclecounter();
         // =========================== matrix part M(j) ===========================
         const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
+        const bool diag = CAUSAL && (j * T + T - 1 > qw0);      // tile j crosses this wave's diagonal
         if (grp == 0) {   // group A spreads its copies over the GEMM steps; whatever has no GEMM to hide behind goes now
             if (!do_g2) {
 #pragma unroll
@@ -393,87 +469,84 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 for (int idx = CPW; idx < 2 * CPW; ++idx) issue_copy(2 * j, idx);
             }
         }
-        if (j <= J_w) {
-            __builtin_amdgcn_s_setprio(PASA_MPRIO);
+        __builtin_amdgcn_s_setprio(PASA_MPRIO);
+        // ---- pending product of tile j-1 ----
         if (do_g2) {
-            // ---- second GEMM of tile j-1: (P V)^T, D channels x 32 queries ----
-            const _Float16* lds_v = reinterpret_cast<const _Float16*>(smem + 2 * KT_BYTES + ((j - 1) & 1) * KT_BYTES);
-            h8 a[PRE][CB];
+            if (STRICT) {
+                gemm2(j - 1, no_hook);
+            } else {
+                // the stored output takes its factor block by block, one block ahead of the MFMA chain that adds to it
 #pragma unroll
-            for (int pre = 0; pre < PRE; ++pre)
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    a[pre][cb] = ABL_LD(lds_v + ((2 * pre + lh) * D + 32 * cb + lq) * 8);
-            PASA_FENCE();
-#pragma unroll
-            for (int kk = 0; kk < ((PASA_ABL & 8) ? 1 : 8); ++kk) {
-#pragma unroll
-                for (int cb = 0; cb < CB; ++cb) {
-                    if (PASA_ABL & 2)
-                        asm volatile("" ::"v"(a[kk % PRE][cb]));
-                    else if (STRICT && kk == 0)
-                        O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kk % PRE][cb], Pf[kk], (f16v)0.f, 0, 0, 0);
-                    else
-                        O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[kk % PRE][cb], Pf[kk], O[cb], 0, 0, 0);
-                }
-                PASA_FENCE();
-                if (kk + PRE < 8) {
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-                        a[kk % PRE][cb] = ABL_LD(lds_v + ((2 * (kk + PRE) + lh) * D + 32 * cb + lq) * 8);
-                    PASA_FENCE();
-                }
-                if (grp == 0 && (kk % (8 / CPW)) == 8 / CPW - 1) {
-                    issue_copy(2 * j, kk / (8 / CPW));
-                    PASA_FENCE();
-                }
+                for (int i = 0; i < 16; ++i) O[0][i] *= g_pend;
+                gemm2(j - 1, [&](int n) {
+                    const int cb = n / 8, kk = n % 8;
+                    if (cb + 1 < CB) {
+                        O[cb + 1][2 * kk] *= g_pend;
+                        O[cb + 1][2 * kk + 1] *= g_pend;
+                    }
+                });
             }
         }
+        // ---- S'(j) ----
+        stats_ready = false;
         if (do_g1) {
-            // ---- first GEMM of tile j: S'^T, 128 keys x 32 queries ----
-            const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (j & 1) * KT_BYTES);
-            h8 a[PRE][4];
+            if (STRICT) {
+                // the fp16 combination of the product just finished is folded in behind the MFMAs
+                gemm1(j, [&](int n) {
+                    if (!do_g2) return;
+                    const _Float16 ec = (_Float16)ec_s, ep = (_Float16)ep_s;
+                    const h2 ec2 = {ec, ec}, ep2 = {ep, ep};
 #pragma unroll
-            for (int pre = 0; pre < PRE; ++pre)
+                    for (int e = 0; e < (CB * 8) / NM1; ++e) {
+                        const int item = n * ((CB * 8) / NM1) + e, cb = item >> 3, t = item & 7;
+                        const h2 ot = pack_rn(O[cb][2 * t], O[cb][2 * t + 1]);
+                        if (j == 1) {
+                            O16[cb][t] = ot;
+                        } else {
+                            const h2 a1 = ec2 * ot;               // each packed op rounds to fp16 once
+                            const h2 a2 = ep2 * O16[cb][t];
+                            O16[cb][t] = a1 + a2;
+                        }
+                    }
+                });
+            } else if (EARLY && !diag) {
+                // row sums and maxima of a finished 32-key block are taken behind the MFMAs of the next block
+                gemm1(j, [&](int n) {
+                    const int kb = n / KS - 1, ks = n % KS;
+                    if (kb < 0) return;
+                    constexpr int PER = 16 / KS;
+                    float sacc = ks ? ps[kb] : 0.f, macc = ks ? pm[kb] : -__builtin_inff();
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb)
-                    a[pre][kb] = ABL_LD(lds_k + ((2 * pre + lh) * T + 32 * kb + lq) * 8);
-            PASA_FENCE();
+                    for (int i = ks * PER; i < (ks + 1) * PER; ++i) {
+                        sacc += S[kb][i];
+                        macc = __builtin_fmaxf(macc, S[kb][i]);
+                    }
+                    ps[kb] = sacc;
+                    pm[kb] = macc;
+                });
+                float sacc = 0.f, macc = -__builtin_inff();
 #pragma unroll
-            for (int ks = 0; ks < ((PASA_ABL & 8) ? 1 : KS); ++ks) {
-#pragma unroll
-                for (int kb = 0; kb < 4; ++kb) {
-                    if (PASA_ABL & 2)
-                        asm volatile("" ::"v"(a[ks % PRE][kb]));
-                    else if (ks == 0)
-                        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks % PRE][kb], Qf[ks], (f16v)0.f, 0, 0, 0);
-                    else
-                        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks % PRE][kb], Qf[ks], S[kb], 0, 0, 0);
+                for (int i = 0; i < 16; ++i) {
+                    sacc += S[3][i];
+                    macc = __builtin_fmaxf(macc, S[3][i]);
                 }
-                PASA_FENCE();
-                if (ks + PRE < KS) {
-#pragma unroll
-                    for (int kb = 0; kb < 4; ++kb)
-                        a[ks % PRE][kb] = ABL_LD(lds_k + ((2 * (ks + PRE) + lh) * T + 32 * kb + lq) * 8);
-                    PASA_FENCE();
-                }
-                if (grp == 0 && (ks % (KS / CPW)) == KS / CPW - 1) {
-                    issue_copy(2 * j, CPW + ks / (KS / CPW));
-                    PASA_FENCE();
-                }
+                ps[3] = sacc;
+                pm[3] = macc;
+                stats_ready = true;
+            } else {
+                gemm1(j, no_hook);
             }
         }
-            __builtin_amdgcn_s_setprio(PASA_VPRIO);
-        }
+        __builtin_amdgcn_s_setprio(PASA_VPRIO);
         if (PASA_ABL & 16) { t1 = __builtin_readcyclecounter(); tM += t1 - t0; }
         if (grp == 1) drain_copies();
         __syncthreads();
         if (PASA_ABL & 16) { t0 = __builtin_readcyclecounter(); tB += t0 - t1; }
         if (grp == 1 && !(j < J_w && !(PASA_ABL & 1))) issue_slot(2 * j + 2);   // no vector part to spread them over
+
+        // =========================== vector part V(j) ===========================
         if (j < J_w && !(PASA_ABL & 1)) {
             const bool first = (j == 0);
-            if (STRICT && j >= 1) fold16(j - 1);
-
             // ---- S' as stored: fp32, or rounded to fp16 ----
             if (S16) {
 #pragma unroll
@@ -495,20 +568,20 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             // ---- pseudo-average over all 128 keys of the tile (before masking) ----
             float sbar = 0.f;
             if (!NAIVE) {
-                float ps[4];
+                if (!(EARLY && stats_ready)) {
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb) {
-                    ps[kb] = S[kb][0];
+                    for (int kb = 0; kb < 4; ++kb) {
+                        ps[kb] = S[kb][0];
 #pragma unroll
-                    for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
+                        for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
+                    }
                 }
-                float sum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
-                sum = sum32(sum);
+                const float sum = sum32((ps[0] + ps[1]) + (ps[2] + ps[3]));
                 sbar = sum * (1.0f / T);
                 if (STRICT) sbar = (float)(_Float16)sbar;
             }
             // ---- causal mask (diagonal tiles only) ----
-            if (CAUSAL && (j * T + T - 1 > qw0)) {
+            if (diag) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -518,18 +591,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     }
             }
             // ---- local maximum m' ----
-            float mx;
-            {
-                float pm[4];
+            if (!(EARLY && stats_ready)) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
                     pm[kb] = S[kb][0];
 #pragma unroll
                     for (int i = 1; i < 16; ++i) pm[kb] = __builtin_fmaxf(pm[kb], S[kb][i]);
                 }
-                mx = __builtin_fmaxf(__builtin_fmaxf(pm[0], pm[1]), __builtin_fmaxf(pm[2], pm[3]));
-                mx = max32(mx);
             }
+            const float mx = max32(__builtin_fmaxf(__builtin_fmaxf(pm[0], pm[1]), __builtin_fmaxf(pm[2], pm[3])));
             // ---- reference level for exp: local m' (PASA), running max (plain FlashAttention) ----
             float mref = mx, e_old = 0.f;
             if (NAIVE) {
@@ -568,13 +638,12 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         PASA_FENCE();
                     }
                 }
-                lsum = (pl[0] + pl[1]) + (pl[2] + pl[3]);
-                lsum = sum32(lsum);
+                lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
                 if (STRICT) lsum = (float)(_Float16)lsum;
             }
 
             // ---- global recovering (step 3), the running sum (step 4) and the output rescale factor ----
-            float g = 0.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
+            float g = 1.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
             bool drop = false;    // this row's tile j is too far below the running maximum to matter
             if (NAIVE) {
                 l = e_old * l + lsum;
@@ -632,12 +701,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     for (int kk = 0; kk < 8; ++kk)
                         if (drop) Pf[kk] = (h8)(_Float16)0;
                 }
-                if (!first) {
-#pragma unroll
-                    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) O[cb][i] *= g;
-                }
+                g_pend = first ? 1.f : g;     // applied under the next first GEMM, before this tile's product is added
             }
         }
         if (PASA_ABL & 16) { t1 = __builtin_readcyclecounter(); tV += t1 - t0; }
