@@ -192,28 +192,17 @@ __device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
 }
 
 #define PASA_FENCE() __builtin_amdgcn_sched_barrier(0)
-#ifndef PASA_MPRIO
-#define PASA_MPRIO 1
-#endif
-#ifndef PASA_VPRIO
-#define PASA_VPRIO 0
-#endif
-#ifndef PASA_GRP
-#define PASA_GRP(w) ((w) >> 2)
-#endif
-#ifndef PASA_ABL
-#define PASA_ABL 0
-#endif
-#define ABL_LD(p) ((PASA_ABL & 4) ? Qf[0] : *reinterpret_cast<const h8*>(p))
 
 // A workgroup is 8 wavefronts and owns 256 query rows, 32 per wavefront.  Wavefronts 0-3 (group A) and 4-7
 // (group B) sit pairwise on the four SIMDs and run the same program half a tile apart: time is cut into slots
-// separated by workgroup barriers, and in every slot one group is in its matrix part (second GEMM of the previous
-// tile, first GEMM of the next) while the other is in its vector part (softmax statistics, global recovering,
-// output rescale), so the MFMA pipe and the VALU of a SIMD are busy at the same time.
+// separated by workgroup barriers, and in every slot one group is in its matrix part while the other is in its
+// vector part, so the MFMA pipe and the VALU of a SIMD are busy at the same time.
 //
 //   group A:  M(0) V(0) M(1) V(1) ...        group B:  -  M(0) V(0) M(1) ...
-//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]      V(j) = [ statistics, P(j), recovery, rescale ]
+//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]   with, behind the MFMAs of the same wave, the rescale of
+//          the running output (fp32 variants), the row sums / maxima of finished blocks of S'(j) (MIXED), or the fp16
+//          combination of the finished product (STRICT16)
+//   V(j) = [ remaining statistics, exponentials -> P(j), row sum, global recovering scalars ]
 //
 // LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued two slots ahead.
 //
@@ -244,7 +233,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = PASA_GRP(wave);
+    const int grp = wave >> 2;
     const int lq = lane & 31, lh = lane >> 5;
 
     // Work decode.  Workgroups are dispatched in index order and dealt round-robin to the 8 XCDs (index % 8), each
@@ -407,7 +396,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM: n = cb * 8 + kk
     auto gemm1 = [&](int jt, auto&& hook) {   // S'^T of tile jt: 128 keys x 32 queries
         const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (jt & 1) * KT_BYTES);
-        auto frag = [&](int n) { return ABL_LD(lds_k + ((2 * (n % KS) + lh) * T + 32 * (n / KS) + lq) * 8); };
+        auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_k + ((2 * (n % KS) + lh) * T + 32 * (n / KS) + lq) * 8); };
         h8 a[PF];
 #pragma unroll
         for (int n = 0; n < PF; ++n) a[n] = frag(n);
@@ -415,9 +404,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
         for (int n = 0; n < NM1; ++n) {
             const int kb = n / KS, ks = n % KS;
-            if (PASA_ABL & 2)
-                asm volatile("" ::"v"(a[n % PF]));
-            else if (ks == 0)
+            if (ks == 0)
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], (f16v)0.f, 0, 0, 0);
             else
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], S[kb], 0, 0, 0);
@@ -430,7 +417,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     };
     auto gemm2 = [&](int jt, auto&& hook) {   // (P V)^T of tile jt: D channels x 32 queries; runs during M(jt+1)
         const _Float16* lds_v = reinterpret_cast<const _Float16*>(smem + 2 * KT_BYTES + (jt & 1) * KT_BYTES);
-        auto frag = [&](int n) { return ABL_LD(lds_v + ((2 * (n % 8) + lh) * D + 32 * (n / 8) + lq) * 8); };
+        auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_v + ((2 * (n % 8) + lh) * D + 32 * (n / 8) + lq) * 8); };
         h8 a[PF];
 #pragma unroll
         for (int n = 0; n < PF; ++n) a[n] = frag(n);
@@ -438,9 +425,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
         for (int n = 0; n < NM2; ++n) {
             const int cb = n / 8, kk = n % 8;
-            if (PASA_ABL & 2)
-                asm volatile("" ::"v"(a[n % PF]));
-            else if (STRICT && kk == 0)
+            if (STRICT && kk == 0)
                 O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Pf[kk], (f16v)0.f, 0, 0, 0);
             else
                 O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Pf[kk], O[cb], 0, 0, 0);
@@ -453,9 +438,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     };
     auto no_hook = [](int) {};
 
-    long long tM = 0, tV = 0, tB = 0, t0 = 0, t1 = 0;
     for (int j = 0; j <= J_wg; ++j) {
-        if (PASA_ABL & 16) t0 = __builtin_readcyclecounter();
         // =========================== matrix part M(j) ===========================
         const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
         const bool diag = CAUSAL && (j * T + T - 1 > qw0);      // tile j crosses this wave's diagonal
@@ -469,7 +452,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 for (int idx = CPW; idx < 2 * CPW; ++idx) issue_copy(2 * j, idx);
             }
         }
-        __builtin_amdgcn_s_setprio(PASA_MPRIO);
+        __builtin_amdgcn_s_setprio(1);
         // ---- pending product of tile j-1 ----
         if (do_g2) {
             if (STRICT) {
@@ -537,15 +520,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 gemm1(j, no_hook);
             }
         }
-        __builtin_amdgcn_s_setprio(PASA_VPRIO);
-        if (PASA_ABL & 16) { t1 = __builtin_readcyclecounter(); tM += t1 - t0; }
+        __builtin_amdgcn_s_setprio(0);
         if (grp == 1) drain_copies();
         __syncthreads();
-        if (PASA_ABL & 16) { t0 = __builtin_readcyclecounter(); tB += t0 - t1; }
-        if (grp == 1 && !(j < J_w && !(PASA_ABL & 1))) issue_slot(2 * j + 2);   // no vector part to spread them over
+        if (grp == 1 && !(j < J_w)) issue_slot(2 * j + 2);   // no vector part to spread them over
 
         // =========================== vector part V(j) ===========================
-        if (j < J_w && !(PASA_ABL & 1)) {
+        if (j < J_w) {
             const bool first = (j == 0);
             // ---- S' as stored: fp32, or rounded to fp16 ----
             if (S16) {
@@ -656,8 +637,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 ec_s = 1.f;
                 ep_s = 0.f;
             } else if (!STRICT) {
-                const float jm1 = (float)j, jn = (float)(j + 1);
-                const float Fn = (jm1 * F + sbar) / jn;
+                // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division
+                // by j is a multiplication by 1/j here
+                const float jm1 = (float)j, rj = 1.0f / (float)(j + 1);
+                const float Fn = (jm1 * F + sbar) * rj;
                 const float dpp = inva * (F - Fn);
                 const float dpc = inva * (sbar - Fn);
                 const float mn = __builtin_fmaxf(m + dpp, mx + dpc);
@@ -697,6 +680,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
             if (!STRICT) {
                 if (__builtin_amdgcn_ballot_w64(drop) != 0ull) {
+                    // rare; the empty asm keeps the compiler from turning this branch into 32 selects on every tile
+                    asm volatile("" ::: "memory");
 #pragma unroll
                     for (int kk = 0; kk < 8; ++kk)
                         if (drop) Pf[kk] = (h8)(_Float16)0;
@@ -704,17 +689,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 g_pend = first ? 1.f : g;     // applied under the next first GEMM, before this tile's product is added
             }
         }
-        if (PASA_ABL & 16) { t1 = __builtin_readcyclecounter(); tV += t1 - t0; }
         if (grp == 0) drain_copies();
         __syncthreads();
-        if (PASA_ABL & 16) { tB += __builtin_readcyclecounter() - t1; }
     }
     if (grp == 0) __syncthreads();         // group B's last barrier
-    if ((PASA_ABL & 16) && blockIdx.x == 0 && lane == 0 && nonfinite_o != nullptr) {
-        nonfinite_o[wave * 3 + 0] = tM;
-        nonfinite_o[wave * 3 + 1] = tV;
-        nonfinite_o[wave * 3 + 2] = tB;
-    }
 
     // ---------------- final normalisation and store ----------------
     unsigned long long n_bad = 0;
@@ -770,7 +748,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
 template <int D, int VAR>
 hipError_t launch_fwd_cv(const PasaLaunch& p)
 {
-    const bool instr = !(PASA_ABL & 16) && (p.overflow_s != nullptr || p.nonfinite_o != nullptr);
+    const bool instr = p.overflow_s != nullptr || p.nonfinite_o != nullptr;
     if (p.causal) return instr ? launch_fwd<D, VAR, true, true>(p) : launch_fwd<D, VAR, true, false>(p);
     return instr ? launch_fwd<D, VAR, false, true>(p) : launch_fwd<D, VAR, false, false>(p);
 }
