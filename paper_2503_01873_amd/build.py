@@ -38,15 +38,31 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
-    out = (res.stdout + res.stderr)
+    log = (res.stdout + res.stderr)
     # hipcc's host pass does not know the packed-fp32 feature name; that warning is expected
-    shown = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+    shown = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("hipcc failed:\n" + log)
     if verbose and shown.strip():
         print(shown)
     return out
 
 
+PROBE = os.path.join(PKG, "probe_mfma_sustained")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """Builds the stand-alone MFMA sustained-rate probe (a measurement tool, not part of libpasa)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", os.path.join(CSRC, "probe_mfma_sustained.hip"), "-o", PROBE]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+    return PROBE
+
+
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))
+    print(build_probe(verbose=True))
