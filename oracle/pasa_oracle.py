@@ -37,6 +37,10 @@ Readings taken where the paper is silent or inconsistent:
     constant may be removed from a row's scores).  Query head h reads KV head h // (Hq // Hkv).
   * In the default shift mode the matrix M is never formed: the tile mean is taken exactly (fp64),
     K' is rounded to fp16 once.  shift="gemm_m" forms M in fp16 and does the GEMM of Alg. 1 literally.
+  * A sequence length that is not a multiple of the tile size (the paper's own Qwen2 case has 5676 keys; its
+    handling is not stated): the last tile uses its own key count as the divisor of both the key mean and the
+    pseudo-average Sbar', so that Eq. (14) still holds for it; the global pseudo-average F weighs it like any
+    other tile (F is only a reference level).
 """
 from __future__ import annotations
 
@@ -135,19 +139,22 @@ def shift_keys(K: np.ndarray, beta: float, scale: float, T: int = 128, mode: str
     mode "gemm_m": K'^T = fl16(K^T M16), M16 = fl16(M) entrywise, the literal GEMM of Alg. 1.
     """
     N, d = K.shape
-    assert N % T == 0
-    K64 = K.astype(np.float64).reshape(N // T, T, d)
+    K64 = K.astype(np.float64)
     if mode == "mean":
-        kbar = K64.sum(axis=1, keepdims=True) / T          # exact: 128 fp16 values fit fp64
-        Kp = (K64 - beta * kbar) * scale
+        Kp = np.empty((N, d))
+        for t0 in range(0, N, T):                           # a ragged last tile uses its own key count
+            tile = K64[t0:t0 + T]
+            kbar = tile.sum(axis=0, keepdims=True) / tile.shape[0]   # exact: at most 128 fp16 values fit fp64
+            Kp[t0:t0 + T] = (tile - beta * kbar) * scale
     elif mode == "gemm_m":
+        assert N % T == 0
         M16 = fl(shift_matrix(beta, T, 1.0 / scale), "f16")
         # (K_j^T M)[c, q] = sum_p K_j[p, c] M[p, q]  ->  K'_j = M^T K_j
-        Kp = np.einsum("pq,jpc->jqc", M16, K64)
+        Kp = np.einsum("pq,jpc->jqc", M16, K64.reshape(N // T, T, d)).reshape(N, d)
     else:
         raise ValueError(mode)
     with np.errstate(over="ignore"):
-        return Kp.reshape(N, d).astype(_NP[fmt])
+        return Kp.astype(_NP[fmt])
 
 
 # ----------------------------------------------------------------------------------------------
@@ -184,11 +191,10 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
     V64 = np.asarray(V).astype(np.float64)
     N, d = K.shape
     R = Q64.shape[0]
-    assert N % T == 0
     Kp64 = shift_keys(np.asarray(K), beta, scale, T, shift, policy.K).astype(np.float64)
     inva = float(fl(beta / (1.0 - beta), st))
     rows = row0 + np.arange(R)
-    ntile = (rows // T + 1) if causal else np.full(R, N // T)
+    ntile = (rows // T + 1) if causal else np.full(R, -(-N // T))
 
     F = np.zeros(R)
     m = np.zeros(R)
@@ -201,15 +207,16 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
             a = np.nonzero(ntile > jt)[0]          # rows that still have this tile
             Kt = Kp64[jt * T:(jt + 1) * T]
             Vt = V64[jt * T:(jt + 1) * T]
+            Tv = Kt.shape[0]                                            # keys in this tile (< T only in a ragged tail)
             S = fl(Q64[a] @ Kt.T, pS)                                   # first GEMM
             fin = np.isfinite(S)
             s_seen += S.size
             s_nonfinite += int(S.size - fin.sum())
             if fin.any():
                 smax = max(smax, float(np.abs(S[fin]).max()))
-            Sbar = fl(S.sum(axis=1) / T, st)                            # pseudo-average, all T keys
+            Sbar = fl(S.sum(axis=1) / Tv, st)                           # pseudo-average, all keys of the tile
             if causal:
-                keys = jt * T + np.arange(T)
+                keys = jt * T + np.arange(Tv)
                 S = np.where(keys[None, :] > rows[a][:, None], -np.inf, S)
             mloc = S.max(axis=1)                                        # m'
             P = fl(np.exp(fl(S - mloc[:, None], pS)), pP)
@@ -256,9 +263,8 @@ def fa_rows(Q, K, V, scale: float, causal: bool, T: int = 128, policy: Policy = 
     V64 = np.asarray(V).astype(np.float64)
     N, d = K64.shape
     R = Q64.shape[0]
-    assert N % T == 0
     rows = row0 + np.arange(R)
-    ntile = (rows // T + 1) if causal else np.full(R, N // T)
+    ntile = (rows // T + 1) if causal else np.full(R, -(-N // T))
     m = np.full(R, -np.inf)
     l = np.zeros(R)
     O = np.zeros((R, d))
@@ -274,7 +280,7 @@ def fa_rows(Q, K, V, scale: float, causal: bool, T: int = 128, policy: Policy = 
                 smax = max(smax, float(np.abs(Sraw[fin]).max()))
             S = fl(Sraw * scale, st)                                    # Eq. (2)
             if causal:
-                keys = jt * T + np.arange(T)
+                keys = jt * T + np.arange(S.shape[1])
                 S = np.where(keys[None, :] > rows[a][:, None], -np.inf, S)
             mnew = np.maximum(m[a], S.max(axis=1))                      # Eq. (4)
             P = fl(np.exp(fl(S - mnew[:, None], st)), pP)               # Eq. (5)

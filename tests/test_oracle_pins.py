@@ -231,6 +231,33 @@ def test_pasa_fp64_equals_plain_definition(causal, T, beta):
     assert np.array_equal(part, got[40:56])
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,T", [(100, 32), (77, 16), (130, 128), (5, 8)])
+def test_pasa_fp64_ragged_tail_equals_plain_definition(causal, N, T):
+    rng = np.random.default_rng(N * 7 + T)
+    d = 8
+    Q = (rng.standard_normal((N, d)) + 1.0).astype(np.float16)
+    K = (rng.standard_normal((N, d)) + np.repeat(rng.uniform(-6, 6, -(-N // T)), T)[:N, None]).astype(np.float16)
+    V = rng.standard_normal((N, d)).astype(np.float16)
+    gold = po.attention_fp64(Q, K, V, 0.35, causal)
+    for beta in (0.0, 0.9375, 63.5 / 64.5):
+        got = po.pasa_rows(Q, K, V, 0.35, causal, beta, T, po.EXACT64)
+        assert (got != gold.astype(np.float16)).mean() < 0.005, beta
+        assert np.abs(got.astype(np.float64) - gold).max() < 2e-3
+    fa = po.fa_rows(Q, K, V, 0.35, causal, T, po.EXACT64)
+    assert np.abs(fa.astype(np.float64) - gold).max() < 2e-3
+    # low precision still close on a ragged length
+    lo = po.pasa_rows(Q, K, V, 0.35, causal, 63.5 / 64.5, T, po.MIXED)
+    assert po.rmse(lo, gold) < 2e-2
+
+
+def test_shift_keys_ragged_tail_uses_its_own_count():
+    K = np.array([[2, 4], [4, 8], [6, 0], [8, 4], [10, 2], [30, 6]], np.float16)   # T = 4: tail has 2 keys
+    got = po.shift_keys(K, 0.5, 1.0, T=4).astype(np.float64)
+    assert np.array_equal(got[:4], K[:4].astype(np.float64) - 0.5 * np.array([[5.0, 4.0]]))
+    assert np.array_equal(got[4:], K[4:].astype(np.float64) - 0.5 * np.array([[20.0, 4.0]]))
+
+
 def test_pasa_fp64_gemm_m_mode_also_exact():
     rng = np.random.default_rng(8)
     N, d, T = 64, 8, 16
