@@ -8,6 +8,8 @@
  * its own mean along the sequence and scaled (Eq. (10), (11)), which leaves every softmax row unchanged
  * (Eq. (9)); a per-row global recovering step re-aligns the running maximum, sum and output across
  * tiles (Eq. (13)-(15), Algorithm 1 steps 1-4) so that half-precision scores stay far below 65504.
+ * N need not be a multiple of 128: a ragged last tile uses its own key count as the divisor of the tile
+ * mean and of the pseudo-average, which keeps Eq. (14) valid for it (the paper does not state this case).
  *
  * Layouts.  q, o: [B, Hq, N, d];  k, v: [B, Hkv, N, d].  IEEE fp16, row-major, contiguous, DEVICE
  * pointers, 16-byte aligned.  Query head h reads KV head h / (Hq / Hkv) (grouped-query attention; the
@@ -34,7 +36,7 @@ extern "C" {
 typedef enum {
     PASA_OK = 0,
     PASA_EINVAL = 1,       /* null or misaligned pointer, non-positive size, Hq % Hkv != 0, bad scale / beta / variant */
-    PASA_EUNSUPPORTED = 2, /* d not in {64, 128}, N not a multiple of 128, N > 262144, shift_tile != 128 */
+    PASA_EUNSUPPORTED = 2, /* d not in {64, 128}, N > 262144, shift_tile != 128 */
     PASA_ELAUNCH = 3,      /* the HIP runtime refused an allocation or a launch */
     PASA_EWORKSPACE = 4    /* workspace missing, misaligned or smaller than pasa_attn_fwd_workspace() */
 } pasa_status;
@@ -66,7 +68,7 @@ int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
                   int B, int Hq, int Hkv, int N, int d, int causal, float scale, void* stream);
 
 /* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes (shifted keys K' and re-tiled values,
- * both fp16: 4*B*Hkv*N*d bytes).  Returns 0 if the sizes are invalid. */
+ * both fp16: 4*B*Hkv*ceil(N/128)*128*d bytes).  Returns 0 if the sizes are invalid. */
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,

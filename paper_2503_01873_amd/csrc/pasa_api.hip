@@ -44,7 +44,7 @@ int check_shape(int B, int Hq, int Hkv, int N, int d)
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || N <= 0 || d <= 0) return PASA_EINVAL;
     if (Hq % Hkv != 0) return PASA_EINVAL;
     if (d != 64 && d != 128) return PASA_EUNSUPPORTED;
-    if (N % kShiftTile != 0 || N > kMaxN) return PASA_EUNSUPPORTED;
+    if (N > kMaxN) return PASA_EUNSUPPORTED;
     return PASA_OK;
 }
 
@@ -57,7 +57,7 @@ const char* pasa_status_string(int status)
     switch (status) {
         case PASA_OK: return "ok";
         case PASA_EINVAL: return "invalid argument";
-        case PASA_EUNSUPPORTED: return "unsupported size (d must be 64 or 128, N a multiple of 128 and <= 262144, shift tile 128)";
+        case PASA_EUNSUPPORTED: return "unsupported size (d must be 64 or 128, N <= 262144, shift tile 128)";
         case PASA_ELAUNCH: return "HIP runtime refused an allocation or a kernel launch";
         case PASA_EWORKSPACE: return "workspace missing, misaligned or too small";
         default: return "unknown status";
@@ -89,7 +89,8 @@ double pasa_optimal_beta(double beta0, int n, int tp)
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
 {
     if (check_shape(B, Hq, Hkv, N, d) != PASA_OK) return 0;
-    return (size_t)4 * (size_t)B * (size_t)Hkv * (size_t)N * (size_t)d;
+    const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
+    return (size_t)4 * (size_t)B * (size_t)Hkv * ntile * kShiftTile * (size_t)d;
 }
 
 int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale, void* stream)

@@ -60,13 +60,15 @@ __device__ inline _Float16 double_to_half_rn(double x)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pre-processing kernel.  grid = B*Hkv*(N/128) tiles, 256 threads.
+// Pre-processing kernel.  grid = B*Hkv*ceil(N/128) tiles, 256 threads.
 // plain_out != nullptr: write K' in the plain [.., N, D] layout instead (pasa_shift_keys).
+// A ragged last tile is padded with zero keys and zero values in the workspace.
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
                                                     _Float16* __restrict__ wsout,
-                                                    _Float16* __restrict__ plain_out, double beta, double kscale)
+                                                    _Float16* __restrict__ plain_out, int N, int ntile,
+                                                    double beta, double kscale)
 {
     constexpr int CH = D / 8;            // 16-byte chunks per key
     constexpr int KL = 256 / CH;         // key lanes
@@ -74,8 +76,12 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     __shared__ double psum[KL][D];
     __shared__ _Float16 vs[T][D + 8];    // +8 halfs: rows start 16 bytes apart in bank space
 
-    const size_t tile = blockIdx.x;
-    const _Float16* ksrc = k + tile * (size_t)(T * D);
+    const size_t tile = blockIdx.x;                      // (batch, KV head, key tile)
+    const size_t head = tile / ntile;
+    const int t = (int)(tile % ntile);
+    const int nvalid = (N - t * T) < T ? (N - t * T) : T;    // keys of this tile (< 128 only in a ragged last tile)
+    const size_t src_off = (head * (size_t)N + (size_t)t * T) * D;
+    const _Float16* ksrc = k + src_off;
     const int tid = threadIdx.x;
     const int c8 = tid % CH, kl = tid / CH;
 
@@ -84,19 +90,20 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
         const int n = kl + KL * i;
-        kv[i] = *reinterpret_cast<const h8*>(ksrc + n * D + 8 * c8);
+        kv[i] = n < nvalid ? *reinterpret_cast<const h8*>(ksrc + n * D + 8 * c8) : (h8)(_Float16)0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s[e] += (double)kv[i][e];   // exact: fp16 values, 128 terms
+        for (int e = 0; e < 8; ++e) s[e] += (double)kv[i][e];   // exact: fp16 values, at most 128 terms
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) psum[kl][8 * c8 + e] = s[e];
 
     if (v != nullptr) {
-        const _Float16* vsrc = v + tile * (size_t)(T * D);
+        const _Float16* vsrc = v + src_off;
 #pragma unroll
         for (int i = 0; i < KPT; ++i) {
             const int n = kl + KL * i;
-            *reinterpret_cast<h8*>(&vs[n][8 * c8]) = *reinterpret_cast<const h8*>(vsrc + n * D + 8 * c8);
+            *reinterpret_cast<h8*>(&vs[n][8 * c8]) =
+                n < nvalid ? *reinterpret_cast<const h8*>(vsrc + n * D + 8 * c8) : (h8)(_Float16)0;
         }
     }
     __syncthreads();
@@ -104,9 +111,9 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     double mean[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        double t = 0;
-        for (int r = 0; r < KL; ++r) t += psum[r][8 * c8 + e];
-        mean[e] = t / (double)T;
+        double tot = 0;
+        for (int r = 0; r < KL; ++r) tot += psum[r][8 * c8 + e];
+        mean[e] = tot / (double)nvalid;      // the tile's own key count, so that Eq. (14) holds for a ragged tile too
     }
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
@@ -117,12 +124,13 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
             // three separately rounded fp64 operations (no contraction): beta*mean, K - that, * kscale
             const double bm = __dmul_rn(beta, mean[e]);
             const double df = __dsub_rn((double)kv[i][e], bm);
-            out[e] = double_to_half_rn(__dmul_rn(df, kscale));
+            out[e] = n < nvalid ? double_to_half_rn(__dmul_rn(df, kscale)) : (_Float16)0;   // padding keys: exact zeros
         }
-        if (plain_out != nullptr)
-            *reinterpret_cast<h8*>(plain_out + tile * (size_t)(T * D) + n * D + 8 * c8) = out;
-        else
+        if (plain_out != nullptr) {
+            if (n < nvalid) *reinterpret_cast<h8*>(plain_out + src_off + n * D + 8 * c8) = out;
+        } else {
             *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)c8 * T + n) * 8) = out;
+        }
     }
 
     if (v != nullptr) {
@@ -265,16 +273,21 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     const int b = grp_id / Hkv, hk_ = grp_id % Hkv;
     const int hq = hk_ * G + hin;
     const int hk = hk_;
-    const int ntile = N / T;
+    const int ntile = (N + T - 1) / T;
+    const int tail_keys = N % T;           // keys of a ragged last tile (0: none)
+    const float inv_tail = 1.0f / (float)(tail_keys ? tail_keys : T);
 
     const int q0 = qt * RWG;
     const int qw0 = q0 + wave * RW;
-    const bool wave_valid = qw0 < N;       // N is a multiple of 128 and a wave owns 32 rows: all or nothing
+    const bool wave_valid = qw0 < N;       // the wave owns at least one real row
     int last_row_wg = q0 + RWG - 1;
     if (last_row_wg > N - 1) last_row_wg = N - 1;
+    int last_row_w = qw0 + RW - 1;
+    if (last_row_w > N - 1) last_row_w = N - 1;
     const int J_wg = CAUSAL ? (last_row_wg / T + 1) : ntile;
-    const int J_w = wave_valid ? (CAUSAL ? ((qw0 + RW - 1) / T + 1) : ntile) : 0;
+    const int J_w = wave_valid ? (CAUSAL ? (last_row_w / T + 1) : ntile) : 0;
     const int row = qw0 + lq;
+    const bool row_valid = row < N;        // rows past the end compute on zero queries and are never stored
 
     const _Float16* qbase = q + ((size_t)(b * Hq + hq) * N) * D;
     const char* wsbase = ws + ((size_t)(b * Hkv + hk) * ntile) * TILE_BYTES;
@@ -291,7 +304,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     h8 Qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        Qf[ks] = wave_valid ? *reinterpret_cast<const h8*>(qbase + (size_t)row * D + 16 * ks + 8 * lh) : (h8)(_Float16)0;
+        Qf[ks] = row_valid ? *reinterpret_cast<const h8*>(qbase + (size_t)row * D + 16 * ks + 8 * lh) : (h8)(_Float16)0;
 
     // per-row state (one query row per lane; both halves of the wave hold copies)
     float F = 0.f, m = NAIVE ? -__builtin_inff() : 0.f, l = 0.f;   // STRICT: always fp16-representable values
@@ -441,7 +454,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     for (int j = 0; j <= J_wg; ++j) {
         // =========================== matrix part M(j) ===========================
         const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
-        const bool diag = CAUSAL && (j * T + T - 1 > qw0);      // tile j crosses this wave's diagonal
+        const bool tail = (tail_keys != 0) && (j == ntile - 1); // ragged last tile: padding keys are masked
+        const bool diag = (CAUSAL && (j * T + T - 1 > qw0)) || (!CAUSAL && tail);   // tile j needs the mask for this wave
         if (grp == 0) {   // group A spreads its copies over the GEMM steps; whatever has no GEMM to hide behind goes now
             if (!do_g2) {
 #pragma unroll
@@ -492,7 +506,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         }
                     }
                 });
-            } else if (EARLY && !diag) {
+            } else if (EARLY && !diag && !tail) {
                 // row sums and maxima of a finished 32-key block are taken behind the MFMAs of the next block
                 gemm1(j, [&](int n) {
                     const int kb = n / KS - 1, ks = n % KS;
@@ -557,18 +571,20 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
                     }
                 }
+                // padding keys of a ragged last tile have K' = 0 and add nothing; the divisor is the tile's own key count
                 const float sum = sum32((ps[0] + ps[1]) + (ps[2] + ps[3]));
-                sbar = sum * (1.0f / T);
+                sbar = sum * (tail ? inv_tail : 1.0f / T);
                 if (STRICT) sbar = (float)(_Float16)sbar;
             }
-            // ---- causal mask (diagonal tiles only) ----
+            // ---- mask: keys after the query (causal, diagonal tiles) or past the end (ragged last tile) ----
             if (diag) {
+                const int last_key = CAUSAL ? row : N - 1;     // causal rows are < N, so the causal mask covers the padding
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = j * T + 32 * kb + 8 * (i >> 2) + 4 * lh + (i & 3);
-                        if (key > row) S[kb][i] = -__builtin_inff();
+                        if (key > last_key) S[kb][i] = -__builtin_inff();
                     }
             }
             // ---- local maximum m' ----
@@ -714,13 +730,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     } else {
                         val = (_Float16)(O16[cb][i >> 1][i & 1] / (_Float16)l);
                     }
-                    if (INSTR) {
+                    if (INSTR && row_valid) {
                         const float fv = (float)val;
                         n_bad += (fv != fv || __builtin_fabsf(fv) == __builtin_inff()) ? 1u : 0u;
                     }
                     out[r] = val;
                 }
-                *reinterpret_cast<h4*>(obase + (size_t)row * D + 32 * cb + 8 * gq + 4 * lh) = out;
+                if (row_valid) *reinterpret_cast<h4*>(obase + (size_t)row * D + 32 * cb + 8 * gq + 4 * lh) = out;
             }
     }
     if (INSTR) {
@@ -770,13 +786,14 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, hipStream_t stream)
 {
-    const dim3 grid((unsigned)((size_t)B * Hkv * (N / T)));
+    const int ntile = (N + T - 1) / T;
+    const dim3 grid((unsigned)((size_t)B * Hkv * ntile));
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, beta, kscale);
+                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, beta, kscale);
+                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale);
     return hipGetLastError();
 }
 

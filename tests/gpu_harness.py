@@ -23,7 +23,9 @@ def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False,
     B, Hq, N, d = q.shape
     Hkv = k.shape[1]
     tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (q, k, v))
-    to = torch.full_like(tq, float("nan"))
+    guard = 4096                        # sentinel elements after the output: nothing may write past its end
+    flat = torch.full((tq.numel() + guard,), float("nan"), dtype=torch.float16, device=dev)
+    to = flat[:tq.numel()].view(tq.shape)
     cnt = torch.zeros(2, dtype=torch.int64, device=dev) if counters else None
     stream = torch.cuda.current_stream()
     if entry == "plain":
@@ -42,6 +44,7 @@ def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False,
         else:
             raise ValueError(entry)
     torch.cuda.synchronize()
+    assert bool(torch.isnan(flat[tq.numel():]).all()), "the kernel wrote past the end of the output"
     return to.cpu().numpy(), (cnt.cpu().numpy() if counters else None)
 
 

@@ -64,7 +64,8 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
 def test_workspace_size():
     assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128
     assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 96) == 0
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 0
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 4 * 4 * 8192 * 128    # ragged last tile is padded
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64
     assert P.pasa_attn_fwd_workspace(1, 28, 5, 8192, 128) == 0
 
 
@@ -89,7 +90,7 @@ def _ex(**over):
     (dict(B=0), 1), (dict(N=0), 1), (dict(N=-128), 1), (dict(Hq=3), 1), (dict(Hkv=0), 1),
     (dict(scale=0.0), 1), (dict(scale=-1.0), 1), (dict(scale=float("nan")), 1), (dict(scale=float("inf")), 1),
     (dict(causal=2), 1), (dict(variant=4), 1), (dict(variant=-1), 1), (dict(beta=1.0), 1), (dict(beta=float("nan")), 1),
-    (dict(d=96), 2), (dict(d=256), 2), (dict(N=200), 2), (dict(N=262144 + 128), 2), (dict(shift_tile=64), 2),
+    (dict(d=96), 2), (dict(d=256), 2), (dict(N=262144 + 128), 2), (dict(shift_tile=64), 2),
     (dict(ws=0), 4), (dict(ws=WS + 16), 4), (dict(wsb=1024), 4),
 ])
 def test_attn_fwd_ex_rejects_bad_arguments(over, want):
@@ -98,12 +99,12 @@ def test_attn_fwd_ex_rejects_bad_arguments(over, want):
 
 def test_other_entry_points_reject_bad_arguments():
     assert P.pasa_attn_fwd(0, K, V, O, 1, 4, 2, 256, 64, 0, 0.125, check=False) == 1
-    assert P.pasa_attn_fwd(Q, K, V, O, 1, 4, 2, 250, 64, 0, 0.125, check=False) == 2
+    assert P.pasa_attn_fwd(Q, K, V, O, 1, 4, 2, 256, 96, 0, 0.125, check=False) == 2
     assert P.pasa_attn_fwd(Q, K, V, O, 1, 4, 3, 256, 64, 0, 0.125, check=False) == 1
     assert P.pasa_shift_keys(0, O, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_shift_keys(K, K, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_shift_keys(K, O, 1, 2, 256, 64, 1.0, 0.125, check=False) == 1
-    assert P.pasa_shift_keys(K, O, 1, 2, 100, 64, 0.5, 0.125, check=False) == 2
+    assert P.pasa_shift_keys(K, O, 1, 2, 256, 32, 0.5, 0.125, check=False) == 2
     assert P.pasa_prepare_kv(K, V, 1, 2, 256, 64, 0.125, WS, 16, check=False) == 4
     assert P.pasa_prepare_kv(K, 0, 1, 2, 256, 64, 0.125, WS, 1 << 20, check=False) == 1
     assert P.pasa_attn_fwd_prepared(Q, Q, 1, 4, 2, 256, 64, 0, 0.125, WS, 1 << 20, check=False) == 1

@@ -45,6 +45,21 @@ def test_shift_keys_bit_exact(d, beta, kscale):
     assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
 
 
+@pytest.mark.parametrize("N,d", [(1, 64), (77, 128), (300, 64), (511, 128)])
+def test_shift_keys_ragged_bit_exact(N, d):
+    import torch
+    rng = np.random.default_rng(N * d)
+    k = (rng.standard_normal((1, 2, N, d)) * 4 + rng.uniform(-80, 80, (1, 2, 1, d))).astype(np.float16)
+    tk = torch.from_numpy(k).cuda()
+    flat = torch.full((k.size + 1024,), float("nan"), dtype=torch.float16, device="cuda")
+    out = flat[:k.size].view(tk.shape)
+    P.pasa_shift_keys(tk, out, 1, 2, N, d, BETA, 0.125)
+    torch.cuda.synchronize()
+    want = np.stack([[po.shift_keys(k[0, h], BETA, 0.125) for h in range(2)]])
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), want.view(np.uint16))
+    assert bool(torch.isnan(flat[k.size:]).all())
+
+
 # ------------------------------------------------------------------ workload 1: the stated bars
 
 @pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16])
@@ -184,6 +199,56 @@ def test_edge_sizes(N, d, causal):
         assert np.array_equal(o[:, :, 0], v[:, [0, 0], 0])
 
 
+# ------------------------------------------------------------------ sequence lengths that are not a multiple of the tile
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(1, 64), (5, 128), (100, 64), (129, 128), (200, 64), (255, 128), (257, 64),
+                                 (383, 128), (500, 128), (1000, 64)])
+def test_ragged_lengths(N, d, causal):
+    rng = np.random.default_rng(7 * N + d)
+    q = rng.standard_normal((1, 4, N, d)).astype(np.float16)
+    k = (rng.standard_normal((1, 2, N, d)) + 2.5).astype(np.float16)
+    v = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    o, cnt = gpu_attn(q, k, v, causal, scale, P.MIXED, counters=True)
+    ref = po.pasa_bhnd(q, k, v, scale, causal, BETA, 128, po.MIXED)
+    c = compare(o, ref)
+    print(N, d, causal, c)
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    assert c["maxabs"] <= 2e-3
+    gold = po.attention_fp64_bhnd(q, k, v, scale, causal)
+    r_gpu, r_or = po.rmse(o, gold), po.rmse(ref, gold)      # the method's own error: the GPU must not add to it
+    assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
+    if causal:
+        assert np.array_equal(o[:, :, 0], v[:, [0, 0, 1, 1], 0])
+
+
+@pytest.mark.parametrize("variant", [P.STRICT16, P.S16])
+@pytest.mark.parametrize("N,causal", [(200, True), (333, False)])
+def test_ragged_lengths_other_variants(N, causal, variant):
+    w = _small(1, N)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, _ = gpu_attn(q, k, v, causal, scale, variant)
+    ref = po.pasa_bhnd(q, k, v, scale, causal, BETA, 128, ORACLE_POLICY[variant])
+    c = compare(o, ref)
+    print(VARIANT_NAME[variant], N, causal, c)
+    assert np.isfinite(o).all()
+    assert c["maxabs"] <= 2e-3
+
+
+def test_ragged_naive16_matches_oracle():
+    rng = np.random.default_rng(99)
+    N, d = 300, 128
+    q = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    k = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    o, _ = gpu_attn(q, k, v, False, scale, P.NAIVE16)
+    ref = po.fa_bhnd(q, k, v, scale, False, 128, po.PARTIAL16)
+    assert compare(o, ref)["maxabs"] <= 2e-3
+
+
 # ------------------------------------------------------------------ full sizes, sampled, in the benchmark's launch configuration
 
 def _sampled_check(w, variant, units, tol_p999=2e-3):
@@ -222,7 +287,7 @@ def _sampled_check(w, variant, units, tol_p999=2e-3):
     for b, h, r0 in units:
         kk, vv = host_kv[(b, h // w.group)]
         qq = host_q[(b, h)][r0:r0 + 128]
-        nk = r0 + 128 if w.causal else w.N
+        nk = min(r0 + 128, w.N) if w.causal else w.N      # r0 is a multiple of 128: whole tiles, or the true ragged tail
         ref = po.pasa_rows(qq, kk[:nk], vv[:nk], scale, w.causal, BETA, 128, ORACLE_POLICY[variant], r0)
         gold = po.attention_fp64(qq, kk[:nk], vv[:nk], scale, w.causal, r0)
         o = to[b, h, r0:r0 + 128].cpu().numpy()
@@ -250,6 +315,12 @@ def test_full_size_qwen_workload_sampled(variant):
     units = [(0, 0, 0), (0, 6, 128), (0, 13, 4096 - 128), (0, 20, 5504), (0, 27, w.N - 128)]
     # STRICT16: one-ulp fp16 flips of Sbar' move a tile's weight by up to 63.5 ulp; only the bulk agrees
     _sampled_check(w, variant, units, tol_p999=2e-3 if variant == P.MIXED else 1e-2)
+
+
+def test_paper_qwen2_sequence_length_5676_sampled():
+    # the sequence length of the paper's Qwen2-7B overflow case (section 2.1); 5676 = 44 * 128 + 44
+    w = workload(3).with_n(5676)
+    _sampled_check(w, P.MIXED, [(0, 0, 0), (0, 13, 2560), (0, 27, 5632)])
 
 
 def test_full_size_svd_workload_sampled():
