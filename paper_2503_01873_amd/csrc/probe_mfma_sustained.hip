@@ -33,6 +33,7 @@ __global__ __launch_bounds__(NW * 64, 2) void mfma_run(const h8* tab, long long*
     }
     f16v c0 = (f16v)0.f, c1 = (f16v)0.f, c2 = (f16v)0.f, c3 = (f16v)0.f;
     __syncthreads();
+    const long long r0 = __builtin_amdgcn_s_memrealtime();   // constant 100 MHz counter
     const long long t0 = __builtin_readcyclecounter();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
@@ -44,7 +45,11 @@ __global__ __launch_bounds__(NW * 64, 2) void mfma_run(const h8* tab, long long*
         }
     }
     const long long t1 = __builtin_readcyclecounter();
-    if (blockIdx.x == 0 && lane == 0) cycles[threadIdx.x >> 6] = t1 - t0;
+    const long long r1 = __builtin_amdgcn_s_memrealtime();
+    if (blockIdx.x == 0 && lane == 0) {
+        cycles[threadIdx.x >> 6] = t1 - t0;
+        cycles[8 + (threadIdx.x >> 6)] = r1 - r0;
+    }
     const float r = c0[0] + c1[1] + c2[2] + c3[3];
     if (r == 12345.678f) sink[threadIdx.x] = r;   // keeps the accumulators live
 }
@@ -64,15 +69,15 @@ static void run(const char* name, const h8* tab, long long* cycles, float* sink,
     CHECK(hipEventSynchronize(e1));
     float ms;
     CHECK(hipEventElapsedTime(&ms, e0, e1));
-    long long h[8];
+    long long h[16];
     CHECK(hipMemcpy(h, cycles, sizeof(h), hipMemcpyDeviceToHost));
-    (void)h;
     const double n_mfma = (double)ncu * NW * iters * 32;
     const double tflops = n_mfma * 32768 / ms / 1e9;
     // a SIMD retires one 32x32x16 MFMA (32768 FLOP) per 32 cycles when the pipe never idles, so the rate implies the clock
     const double clock_ghz = tflops * 1e12 / ((double)ncu * 4 * 1024) / 1e9;
-    printf("%-28s %d wave(s)/SIMD  %8.3f ms  %7.0f TFLOP/s  %5.1f %% of 2500  implied shader clock >= %.2f GHz\n", name,
-           NW / 4, ms, tflops, tflops / 25.0, clock_ghz);
+    printf("%-28s %d wave(s)/SIMD  %8.3f ms  %7.0f TFLOP/s  %5.1f %% of 2500  implied shader clock >= %.2f GHz"
+           "   [wave 0: cycle counter %lld, 100 MHz counter %lld, ratio %.2f]\n", name,
+           NW / 4, ms, tflops, tflops / 25.0, clock_ghz, h[0], h[8], (double)h[0] / (double)(h[8] ? h[8] : 1));
 }
 
 int main()
