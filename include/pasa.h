@@ -36,7 +36,7 @@ extern "C" {
 typedef enum {
     PASA_OK = 0,
     PASA_EINVAL = 1,       /* null or misaligned pointer, non-positive size, Hq % Hkv != 0, bad scale / beta / variant */
-    PASA_EUNSUPPORTED = 2, /* d not in {64, 128}, N > 262144, shift_tile != 128 */
+    PASA_EUNSUPPORTED = 2, /* d not in {64, 128}, a length > 262144, shift_tile != 128, PASA_SHIFT_MATRIX with N % 128 != 0 */
     PASA_ELAUNCH = 3,      /* the HIP runtime refused an allocation or a launch */
     PASA_EWORKSPACE = 4    /* workspace missing, misaligned or smaller than pasa_attn_fwd_workspace() */
 } pasa_status;
@@ -51,15 +51,27 @@ typedef enum {
     PASA_S16 = 3       /* shifted like MIXED, S' rounded to fp16 as it leaves the matrix core, statistics and O fp32 */
 } pasa_variant;
 
+/* How the key pre-processing loop of Algorithm 1 forms K' (Eq. (10), (11)). */
+typedef enum {
+    PASA_SHIFT_MEAN = 0,   /* K' = fp16((K - beta * mean_tile(K)) * scale): mean by reduction in fp64, one rounding.
+                              The shifting matrix is never formed, so its entries are never rounded. */
+    PASA_SHIFT_MATRIX = 1  /* Algorithm 1 as printed: K'^T = K^T M with every entry of M = I/alpha - beta J/(128 alpha),
+                              alpha = 1/scale, rounded to fp16 first (the rounding that section 2.3 and Eq. (20)-(22)
+                              analyse); the product is exact (fp64) and rounded to fp16 once.  Evaluated as
+                              (a - b) K + b sum_tile(K) with a, b the rounded diagonal and off-diagonal entry, which
+                              is the same contraction.  Needs N % 128 == 0. */
+} pasa_shift_mode;
+
 typedef struct {
-    float beta;        /* shift fraction of Eq. (10).  < 0: library default 63.5/64.5 (invariance beta/(1-beta) = 63.5,
-                          the fp16 value of the invariance of the paper's adopted beta = 0.984497);  0: plain FlashAttention;
-                          otherwise must lie in [0, 1). */
+    float beta;        /* shift fraction of Eq. (10).  < 0: library default -- by mean 63.5/64.5 (invariance beta/(1-beta) =
+                          63.5, the fp16 value of the invariance of the paper's adopted beta), by matrix the paper's
+                          adopted beta = 0.984497 (Table 3);  0: plain FlashAttention;  otherwise must lie in [0, 1). */
     int variant;       /* a pasa_variant */
     int shift_tile;    /* keys per pseudo-average group; 0 or 128 (the only supported size) */
     unsigned long long* overflow_s;  /* optional DEVICE counter (caller zeroes it): score-tile entries whose magnitude
                                         exceeds 65504 where they would be stored as fp16.  NULL: not counted. */
     unsigned long long* nonfinite_o; /* optional DEVICE counter (caller zeroes it): inf/NaN entries written to o. */
+    int shift_mode;    /* a pasa_shift_mode */
 } pasa_opts;
 
 /* Default configuration: PASA_MIXED, default beta.  Allocates and frees its workspace in stream order
@@ -73,7 +85,7 @@ size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
  * at least pasa_attn_fwd_workspace() bytes; contents on return are unspecified).  opts == NULL means
- * {beta = -1, PASA_MIXED, 128, NULL, NULL}.  Performs no allocation. */
+ * {beta = -1, PASA_MIXED, 128, NULL, NULL, PASA_SHIFT_MEAN}.  Performs no allocation. */
 int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
                      int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                      const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
@@ -89,12 +101,29 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
 int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                            const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
 
+/* The main loops of Algorithm 1 for a chunk of queries against a prepared workspace of N keys (the problem
+ * statement of section 1.1 allows different query and key lengths S1 != S2; the paper does not elaborate).
+ * q, o: [B, Hq, Nq, d].  Query row r sits at sequence position row0 + r: with causal != 0 it sees the keys
+ * n <= row0 + r (row0 = N - Nq aligns the last query with the last key; positions past N - 1 see all keys);
+ * with causal == 0 every row sees all N keys and row0 is ignored.  Covers cross-attention, prefill in chunks and
+ * decoding against a cache.  pasa_attn_fwd_prepared(..., N, ...) is the case Nq = N, row0 = 0.  A row's result
+ * does not depend on the other rows of its chunk: splitting a sequence at multiples of 32 rows gives bit-identical
+ * output, any other split the same up to the fp32 summation order of the pseudo-average.  PASA_EINVAL for
+ * Nq <= 0 or row0 < 0; otherwise the rules of pasa_attn_fwd_prepared. */
+int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
+                        float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
+
 /* Key pre-processing alone (Algorithm 1's first loop, Eq. (11)): writes, for every 128-key tile,
  * K'[n, c] = fp16((K[n, c] - beta * mean_tile(K[:, c])) * kscale) to kprime in the plain [B, Hkv, N, d]
  * layout.  The mean and the arithmetic are fp64 and the result is rounded once.  For tests and tools;
  * the attention entry points do this internally in their own tiled layout. */
 int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d,
                     double beta, double kscale, void* stream);
+
+/* The same with PASA_SHIFT_MATRIX: K'^T = fp16(K^T M16), M16 the entrywise fp16 rounding of Eq. (10)'s M with
+ * alpha = 1/kscale.  N must be a multiple of 128. */
+int pasa_shift_keys_matrix(const void* k, void* kprime, int B, int Hkv, int N, int d,
+                           double beta, double kscale, void* stream);
 
 /* Host-only, fp64: solves the optimal accuracy condition beta/(1-beta) = f(beta) (Eq. (16), (20)-(22)) by
  * fixed-point iteration from beta0, for a shifting matrix of size n rounded to format tp

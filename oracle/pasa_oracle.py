@@ -194,7 +194,7 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
     Kp64 = shift_keys(np.asarray(K), beta, scale, T, shift, policy.K).astype(np.float64)
     inva = float(fl(beta / (1.0 - beta), st))
     rows = row0 + np.arange(R)
-    ntile = (rows // T + 1) if causal else np.full(R, -(-N // T))
+    ntile = np.minimum(rows // T + 1, -(-N // T)) if causal else np.full(R, -(-N // T))   # positions past the last key see all keys
 
     F = np.zeros(R)
     m = np.zeros(R)
@@ -264,7 +264,7 @@ def fa_rows(Q, K, V, scale: float, causal: bool, T: int = 128, policy: Policy = 
     N, d = K64.shape
     R = Q64.shape[0]
     rows = row0 + np.arange(R)
-    ntile = (rows // T + 1) if causal else np.full(R, -(-N // T))
+    ntile = np.minimum(rows // T + 1, -(-N // T)) if causal else np.full(R, -(-N // T))   # positions past the last key see all keys
     m = np.full(R, -np.inf)
     l = np.zeros(R)
     O = np.zeros((R, d))

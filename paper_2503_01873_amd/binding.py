@@ -10,6 +10,7 @@ import ctypes
 import os
 
 MIXED, STRICT16, NAIVE16, S16 = 0, 1, 2, 3
+SHIFT_MEAN, SHIFT_MATRIX = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("PASA_LIB") or os.path.join(_PKG, "libpasa.so")
@@ -29,6 +30,7 @@ class pasa_opts(ctypes.Structure):
         ("shift_tile", ctypes.c_int),
         ("overflow_s", ctypes.c_void_p),
         ("nonfinite_o", ctypes.c_void_p),
+        ("shift_mode", ctypes.c_int),
     ]
 
 
@@ -57,8 +59,12 @@ def lib() -> ctypes.CDLL:
     L.pasa_prepare_kv.restype = ci
     L.pasa_attn_fwd_prepared.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_attn_fwd_prepared.restype = ci
+    L.pasa_attn_fwd_chunk.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
+    L.pasa_attn_fwd_chunk.restype = ci
     L.pasa_shift_keys.argtypes = [vp, vp, ci, ci, ci, ci, cd, cd, vp]
     L.pasa_shift_keys.restype = ci
+    L.pasa_shift_keys_matrix.argtypes = [vp, vp, ci, ci, ci, ci, cd, cd, vp]
+    L.pasa_shift_keys_matrix.restype = ci
     L.pasa_optimal_beta.argtypes = [cd, ci, ci]
     L.pasa_optimal_beta.restype = cd
     L.pasa_invariance_rounded.argtypes = [cd, ci, ci]
@@ -121,8 +127,8 @@ def pasa_attn_fwd(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, stream=None, chec
 
 def pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, workspace, workspace_bytes, stream=None,
                      beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
-                     opts_null=False, check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o))
+                     shift_mode=SHIFT_MEAN, opts_null=False, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode))
     st = lib().pasa_attn_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, Hq, Hkv, N, d, int(causal), float(scale),
                                 None if opts_null else ctypes.byref(opts), _ptr(workspace), int(workspace_bytes),
                                 _stream(stream))
@@ -130,8 +136,8 @@ def pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, workspace, wor
 
 
 def pasa_prepare_kv(k, v, B, Hkv, N, d, scale, workspace, workspace_bytes, stream=None, beta=-1.0, variant=MIXED,
-                    shift_tile=128, check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), None, None)
+                    shift_tile=128, shift_mode=SHIFT_MEAN, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), None, None, int(shift_mode))
     st = lib().pasa_prepare_kv(_ptr(k), _ptr(v), B, Hkv, N, d, float(scale), ctypes.byref(opts), _ptr(workspace),
                                int(workspace_bytes), _stream(stream))
     return _check(st, "pasa_prepare_kv", check)
@@ -139,8 +145,8 @@ def pasa_prepare_kv(k, v, B, Hkv, N, d, scale, workspace, workspace_bytes, strea
 
 def pasa_attn_fwd_prepared(q, o, B, Hq, Hkv, N, d, causal, scale, workspace, workspace_bytes, stream=None,
                            beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
-                           check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o))
+                           shift_mode=SHIFT_MEAN, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode))
     st = lib().pasa_attn_fwd_prepared(_ptr(q), _ptr(o), B, Hq, Hkv, N, d, int(causal), float(scale),
                                       ctypes.byref(opts), _ptr(workspace), int(workspace_bytes), _stream(stream))
     return _check(st, "pasa_attn_fwd_prepared", check)
@@ -149,3 +155,18 @@ def pasa_attn_fwd_prepared(q, o, B, Hq, Hkv, N, d, causal, scale, workspace, wor
 def pasa_shift_keys(k, kprime, B, Hkv, N, d, beta, kscale, stream=None, check=True) -> int:
     st = lib().pasa_shift_keys(_ptr(k), _ptr(kprime), B, Hkv, N, d, float(beta), float(kscale), _stream(stream))
     return _check(st, "pasa_shift_keys", check)
+
+
+def pasa_shift_keys_matrix(k, kprime, B, Hkv, N, d, beta, kscale, stream=None, check=True) -> int:
+    st = lib().pasa_shift_keys_matrix(_ptr(k), _ptr(kprime), B, Hkv, N, d, float(beta), float(kscale),
+                                      _stream(stream))
+    return _check(st, "pasa_shift_keys_matrix", check)
+
+
+def pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, workspace, workspace_bytes, stream=None,
+                        beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
+                        shift_mode=SHIFT_MEAN, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode))
+    st = lib().pasa_attn_fwd_chunk(_ptr(q), _ptr(o), B, Hq, Hkv, Nq, row0, N, d, int(causal), float(scale),
+                                   ctypes.byref(opts), _ptr(workspace), int(workspace_bytes), _stream(stream))
+    return _check(st, "pasa_attn_fwd_chunk", check)

@@ -57,7 +57,8 @@ const char* pasa_status_string(int status)
     switch (status) {
         case PASA_OK: return "ok";
         case PASA_EINVAL: return "invalid argument";
-        case PASA_EUNSUPPORTED: return "unsupported size (d must be 64 or 128, N <= 262144, shift tile 128)";
+        case PASA_EUNSUPPORTED:
+            return "unsupported size (d must be 64 or 128, N <= 262144, shift tile 128, N % 128 == 0 for the matrix shift)";
         case PASA_ELAUNCH: return "HIP runtime refused an allocation or a kernel launch";
         case PASA_EWORKSPACE: return "workspace missing, misaligned or too small";
         default: return "unknown status";
@@ -93,15 +94,52 @@ size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
     return (size_t)4 * (size_t)B * (size_t)Hkv * ntile * kShiftTile * (size_t)d;
 }
 
-int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale, void* stream)
+}  // extern "C"
+
+namespace {
+
+// Entries of the shifting matrix M = I/alpha - beta J/(alpha T) of Eq. (10), alpha = 1/kscale, each rounded to
+// fp16: a on the diagonal, b elsewhere.  The pre-processing kernel takes a - b and b.
+void rounded_shift_matrix(double beta, double kscale, double* a_minus_b, double* b)
+{
+    const double alpha = 1.0 / kscale;
+    const double off = beta / (alpha * (double)kShiftTile);
+    const double a16 = round_to_format(1.0 / alpha - off, 11, -14, 15);
+    const double b16 = round_to_format(0.0 - off, 11, -14, 15);
+    *a_minus_b = a16 - b16;    // exact: both are fp16 values
+    *b = b16;
+}
+
+int shift_keys_common(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale,
+                      int matrix_mode, void* stream)
 {
     const int st = check_shape(B, Hkv, Hkv, N, d);
     if (st != PASA_OK) return st;
     if (k == nullptr || kprime == nullptr || !aligned(k, 16) || !aligned(kprime, 16) || k == kprime) return PASA_EINVAL;
     if (!(beta >= 0.0) || !(beta < 1.0) || !isfinite(kscale) || !(kscale > 0.0)) return PASA_EINVAL;
-    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, beta, kscale,
+    double c1 = beta, c2 = kscale;
+    if (matrix_mode) {
+        if (N % kShiftTile != 0) return PASA_EUNSUPPORTED;   // M is a full 128 x 128 matrix
+        rounded_shift_matrix(beta, kscale, &c1, &c2);
+    }
+    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, matrix_mode,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale, void* stream)
+{
+    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, 0, stream);
+}
+
+int pasa_shift_keys_matrix(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale,
+                           void* stream)
+{
+    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, 1, stream);
 }
 
 namespace {
@@ -109,8 +147,9 @@ namespace {
 // Resolved numeric parameters of one call.
 struct Params {
     int variant;
-    double beta;      // shift fraction used by the pre-processing kernel
-    double kscale;    // factor folded into K'
+    double beta;      // shift fraction used by the pre-processing kernel (matrix mode: a - b)
+    double kscale;    // factor folded into K' (matrix mode: b)
+    int matrix_mode;  // K' by the fp16-rounded shifting matrix instead of by the tile mean
     float inva;       // beta/(1-beta) rounded to the statistics precision
     unsigned long long* overflow_s;
     unsigned long long* nonfinite_o;
@@ -119,13 +158,16 @@ struct Params {
 int resolve(const pasa_opts* opts, float scale, Params* out)
 {
     if (!isfinite(scale) || !(scale > 0.f)) return PASA_EINVAL;
-    pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr};
+    pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr, PASA_SHIFT_MEAN};
     if (opts != nullptr) op = *opts;
     if (op.variant < PASA_MIXED || op.variant > PASA_S16) return PASA_EINVAL;
+    if (op.shift_mode != PASA_SHIFT_MEAN && op.shift_mode != PASA_SHIFT_MATRIX) return PASA_EINVAL;
     if (op.shift_tile != 0 && op.shift_tile != kShiftTile) return PASA_EUNSUPPORTED;
     if (!(op.beta < 1.f)) return PASA_EINVAL;              // also rejects NaN
-    // beta and the invariance beta/(1-beta) in fp64; the default makes the invariance exactly 63.5
-    double beta = op.beta < 0.f ? 63.5 / 64.5 : (double)op.beta;
+    // beta and the invariance beta/(1-beta) in fp64.  Default by mean: the invariance is exactly 63.5.  Default by
+    // matrix: the paper's adopted solution of the optimal accuracy condition for fp16 and n = 128 (Table 3).
+    const double beta_default = op.shift_mode == PASA_SHIFT_MATRIX ? 0.984497 : 63.5 / 64.5;
+    double beta = op.beta < 0.f ? beta_default : (double)op.beta;
     double kscale = (double)scale;
     if (op.variant == PASA_NAIVE16) {   // no shift, static scaling applied after the first GEMM (Eq. (1), (2))
         beta = 0.0;
@@ -135,6 +177,8 @@ int resolve(const pasa_opts* opts, float scale, Params* out)
     out->variant = op.variant;
     out->beta = beta;
     out->kscale = kscale;
+    out->matrix_mode = op.shift_mode == PASA_SHIFT_MATRIX;
+    if (out->matrix_mode) rounded_shift_matrix(beta, kscale, &out->beta, &out->kscale);
     out->inva = op.variant == PASA_STRICT16 ? (float)round_to_format(inva_d, 11, -14, 15) : (float)inva_d;
     out->overflow_s = op.overflow_s;
     out->nonfinite_o = op.nonfinite_o;
@@ -157,10 +201,11 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
     if (st != PASA_OK) return st;
     st = check_shape(B, Hkv, Hkv, N, d);
     if (st != PASA_OK) return st;
+    if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;   // M is a full 128 x 128 matrix
     const size_t need = pasa_attn_fwd_workspace(B, Hkv, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
-    const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale,
+    const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, pr.matrix_mode,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
@@ -168,19 +213,29 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
 int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                            const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
 {
+    return pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, opts, workspace, workspace_bytes, stream);
+}
+
+int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
+                        float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
+{
     if (q == nullptr || o == nullptr || !aligned(q, 16) || !aligned(o, 16) || o == q) return PASA_EINVAL;
     if (causal != 0 && causal != 1) return PASA_EINVAL;
+    if (Nq <= 0 || row0 < 0) return PASA_EINVAL;
     Params pr;
     int st = resolve(opts, scale, &pr);
     if (st != PASA_OK) return st;
     st = check_shape(B, Hq, Hkv, N, d);
     if (st != PASA_OK) return st;
+    if (Nq > kMaxN || row0 > kMaxN) return PASA_EUNSUPPORTED;
+    if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
     const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
     PasaLaunch p;
     p.q = q; p.ws = workspace; p.o = o;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.d = d;
+    p.Nq = Nq; p.row0 = causal ? row0 : 0;
     p.causal = causal;
     p.variant = pr.variant;
     p.inva = pr.inva;
@@ -205,6 +260,7 @@ int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B
     if (st != PASA_OK) return st;
     st = check_shape(B, Hq, Hkv, N, d);
     if (st != PASA_OK) return st;
+    if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
     st = check_workspace(workspace, workspace_bytes, pasa_attn_fwd_workspace(B, Hq, Hkv, N, d));
     if (st != PASA_OK) return st;
     st = pasa_prepare_kv(k, v, B, Hkv, N, d, scale, opts, workspace, workspace_bytes, stream);

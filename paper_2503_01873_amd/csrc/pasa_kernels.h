@@ -11,7 +11,8 @@ struct PasaLaunch {
     const void* q;
     const void* ws;   // per (batch, KV head, key tile): shifted-key tile then value tile, fragment-major layout
     void* o;
-    int B, Hq, Hkv, N, d;
+    int B, Hq, Hkv, N, d;   // N: keys
+    int Nq, row0;           // query rows given, and the sequence position of the first of them
     int causal;
     int variant;
     float inva;       // beta/(1-beta), already rounded to the statistics precision
@@ -23,8 +24,12 @@ struct PasaLaunch {
 
 // Shift + re-tile K (and re-tile V when v != nullptr).  plain_out != nullptr: K' goes there in the
 // plain [B,Hkv,N,d] layout and ws is not written.
+// matrix_mode == 0: K' = fp16((K - beta * tile mean) * kscale).
+// matrix_mode == 1: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
+//                   matrix a I + b (J - I) when beta carries a - b and kscale carries b (N % 128 == 0 only).
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
-                            int B, int Hkv, int N, int d, double beta, double kscale, hipStream_t stream);
+                            int B, int Hkv, int N, int d, double beta, double kscale, int matrix_mode,
+                            hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);
 

@@ -68,7 +68,7 @@ template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
                                                     _Float16* __restrict__ wsout,
                                                     _Float16* __restrict__ plain_out, int N, int ntile,
-                                                    double beta, double kscale)
+                                                    double beta, double kscale, int matrix_mode)
 {
     constexpr int CH = D / 8;            // 16-byte chunks per key
     constexpr int KL = 256 / CH;         // key lanes
@@ -112,8 +112,10 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         double tot = 0;
+#pragma unroll 4
         for (int r = 0; r < KL; ++r) tot += psum[r][8 * c8 + e];
-        mean[e] = tot / (double)nvalid;      // the tile's own key count, so that Eq. (14) holds for a ragged tile too
+        // the tile's own key count, so that Eq. (14) holds for a ragged tile too; the matrix form needs the plain sum
+        mean[e] = matrix_mode ? tot : tot / (double)nvalid;
     }
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
@@ -121,10 +123,19 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
         h8 out;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            // three separately rounded fp64 operations (no contraction): beta*mean, K - that, * kscale
-            const double bm = __dmul_rn(beta, mean[e]);
-            const double df = __dsub_rn((double)kv[i][e], bm);
-            out[e] = n < nvalid ? double_to_half_rn(__dmul_rn(df, kscale)) : (_Float16)0;   // padding keys: exact zeros
+            double r;
+            if (matrix_mode) {
+                // K'^T = K^T M with M = a I + b (J - I) entrywise rounded to fp16 (Eq. (10), (11) as a GEMM):
+                // sum_p M[p,q] K[p,c] = (a - b) K[q,c] + b sum_p K[p,c].  Here beta carries (a - b) and kscale
+                // carries b; both products are exact in fp64 and the sum rounds once.
+                r = __dadd_rn(__dmul_rn(beta, (double)kv[i][e]), __dmul_rn(kscale, mean[e]));
+            } else {
+                // three separately rounded fp64 operations (no contraction): beta*mean, K - that, * kscale
+                const double bm = __dmul_rn(beta, mean[e]);
+                const double df = __dsub_rn((double)kv[i][e], bm);
+                r = __dmul_rn(df, kscale);
+            }
+            out[e] = n < nvalid ? double_to_half_rn(r) : (_Float16)0;   // padding keys: exact zeros
         }
         if (plain_out != nullptr) {
             if (n < nvalid) *reinterpret_cast<h8*>(plain_out + src_off + n * D + 8 * c8) = out;
@@ -224,7 +235,7 @@ __device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
-              int Hq, int Hkv, int N, int nqt, float inva, float scale,
+              int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale,
               unsigned long long* ovf_s, unsigned long long* nonfinite_o)
 {
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
@@ -277,19 +288,25 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     const int tail_keys = N % T;           // keys of a ragged last tile (0: none)
     const float inv_tail = 1.0f / (float)(tail_keys ? tail_keys : T);
 
+    // Query row r of the Nq rows given sits at sequence position row0 + r (causal: it sees keys <= its position).
     const int q0 = qt * RWG;
     const int qw0 = q0 + wave * RW;
-    const bool wave_valid = qw0 < N;       // the wave owns at least one real row
+    const bool wave_valid = qw0 < Nq;      // the wave owns at least one real row
     int last_row_wg = q0 + RWG - 1;
-    if (last_row_wg > N - 1) last_row_wg = N - 1;
+    if (last_row_wg > Nq - 1) last_row_wg = Nq - 1;
     int last_row_w = qw0 + RW - 1;
-    if (last_row_w > N - 1) last_row_w = N - 1;
-    const int J_wg = CAUSAL ? (last_row_wg / T + 1) : ntile;
-    const int J_w = wave_valid ? (CAUSAL ? (last_row_w / T + 1) : ntile) : 0;
+    if (last_row_w > Nq - 1) last_row_w = Nq - 1;
+    auto tiles_seen = [&](int r) {         // key tiles a causal row at position row0 + r reaches
+        const int t = (row0 + r) / T + 1;
+        return t < ntile ? t : ntile;
+    };
+    const int J_wg = CAUSAL ? tiles_seen(last_row_wg) : ntile;
+    const int J_w = wave_valid ? (CAUSAL ? tiles_seen(last_row_w) : ntile) : 0;
     const int row = qw0 + lq;
-    const bool row_valid = row < N;        // rows past the end compute on zero queries and are never stored
+    const bool row_valid = row < Nq;       // rows past the end compute on zero queries and are never stored
+    const int pos_w0 = row0 + qw0;         // position of the wave's first row
 
-    const _Float16* qbase = q + ((size_t)(b * Hq + hq) * N) * D;
+    const _Float16* qbase = q + ((size_t)(b * Hq + hq) * Nq) * D;
     const char* wsbase = ws + ((size_t)(b * Hkv + hk) * ntile) * TILE_BYTES;
 
     auto issue_k = [&](int j) {
@@ -455,7 +472,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         // =========================== matrix part M(j) ===========================
         const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
         const bool tail = (tail_keys != 0) && (j == ntile - 1); // ragged last tile: padding keys are masked
-        const bool diag = (CAUSAL && (j * T + T - 1 > qw0)) || (!CAUSAL && tail);   // tile j needs the mask for this wave
+        const bool diag = (CAUSAL && (j * T + T - 1 > pos_w0)) || tail;   // tile j needs the mask for this wave
         if (grp == 0) {   // group A spreads its copies over the GEMM steps; whatever has no GEMM to hide behind goes now
             if (!do_g2) {
 #pragma unroll
@@ -578,7 +595,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
             // ---- mask: keys after the query (causal, diagonal tiles) or past the end (ragged last tile) ----
             if (diag) {
-                const int last_key = CAUSAL ? row : N - 1;     // causal rows are < N, so the causal mask covers the padding
+                int last_key = N - 1;
+                if (CAUSAL && row0 + row < last_key) last_key = row0 + row;
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -597,8 +615,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 }
             }
             const float mx = max32(__builtin_fmaxf(__builtin_fmaxf(pm[0], pm[1]), __builtin_fmaxf(pm[2], pm[3])));
+            // A wave whose rows straddle a tile boundary (chunks not aligned to 32 rows) reaches tile j although its
+            // first rows see none of it: those rows keep their state and add nothing.
+            const bool unseen = CAUSAL && diag && (row0 + row < j * T);
             // ---- reference level for exp: local m' (PASA), running max (plain FlashAttention) ----
-            float mref = mx, e_old = 0.f;
+            float mref = unseen ? 0.f : mx, e_old = 0.f;
             if (NAIVE) {
                 const float mnew = __builtin_fmaxf(m, mx);
                 e_old = exp_nat(m - mnew);
@@ -652,6 +673,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 Lc = 0.f;
                 ec_s = 1.f;
                 ep_s = 0.f;
+            } else if (unseen) {
+                if (STRICT) {     // O <- fp16(0 * 0) + fp16(1 * O)
+                    ec_s = 0.f;
+                    ep_s = 1.f;
+                }
             } else if (!STRICT) {
                 // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division
                 // by j is a multiplication by 1/j here
@@ -715,7 +741,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     if (wave_valid) {
         if (STRICT) fold16(J_w - 1);
         const float oscale = STRICT ? 0.f : exp_nat(Lc) / l;
-        _Float16* obase = o + ((size_t)(b * Hq + hq) * N) * D;
+        _Float16* obase = o + ((size_t)(b * Hq + hq) * Nq) * D;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
@@ -750,14 +776,14 @@ hipError_t launch_fwd(const PasaLaunch& p)
 {
     constexpr int RWG = 256;
     constexpr int LDS_BYTES = 4 * (T * D * 2);
-    const int nqt = (p.N + RWG - 1) / RWG;
+    const int nqt = (p.Nq + RWG - 1) / RWG;
     const dim3 grid((unsigned)(nqt * p.Hq * p.B));
     auto kern = pasa_fwd<D, VAR, CAUSAL, INSTR>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        LDS_BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
-                       (_Float16*)p.o, p.Hq, p.Hkv, p.N, nqt, p.inva, p.scale, p.overflow_s, p.nonfinite_o);
+                       (_Float16*)p.o, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.overflow_s, p.nonfinite_o);
     return hipGetLastError();
 }
 
@@ -784,16 +810,17 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 }  // namespace
 
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
-                            int B, int Hkv, int N, int d, double beta, double kscale, hipStream_t stream)
+                            int B, int Hkv, int N, int d, double beta, double kscale, int matrix_mode,
+                            hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
     const dim3 grid((unsigned)((size_t)B * Hkv * ntile));
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale);
+                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale);
+                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode);
     return hipGetLastError();
 }
 

@@ -16,7 +16,8 @@ def f32(x: float) -> float:
     return float(np.float32(x))
 
 
-def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False, entry="ex"):
+def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False, entry="ex",
+             shift_mode=P.SHIFT_MEAN):
     """Run the HIP path on numpy fp16 inputs [B,H,N,d]; returns (o fp16 numpy, counters or None)."""
     import torch
     dev = torch.device("cuda:0")
@@ -33,7 +34,7 @@ def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False,
     else:
         wsb = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
-        kw = dict(beta=beta, variant=variant)
+        kw = dict(beta=beta, variant=variant, shift_mode=shift_mode)
         if entry == "ex":
             P.pasa_attn_fwd_ex(tq, tk, tv, to, B, Hq, Hkv, N, d, causal, scale, ws, wsb, stream,
                                overflow_s=cnt[0:1] if counters else None,
@@ -46,6 +47,32 @@ def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False,
     torch.cuda.synchronize()
     assert bool(torch.isnan(flat[tq.numel():]).all()), "the kernel wrote past the end of the output"
     return to.cpu().numpy(), (cnt.cpu().numpy() if counters else None)
+
+
+def gpu_attn_chunks(q, k, v, causal, scale, chunks, variant=P.MIXED, beta=-1.0):
+    """K/V prepared once, then one pasa_attn_fwd_chunk call per (first query row, row count, row0) of `chunks`.
+    q: [B,Hq,Nq,d] numpy fp16; each chunk's rows are copied to a buffer of their own.  Returns o [B,Hq,Nq,d]."""
+    import torch
+    dev = torch.device("cuda:0")
+    B, Hq, Nq, d = q.shape
+    Hkv, N = k.shape[1], k.shape[2]
+    tk, tv = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (k, v))
+    wsb = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+    P.pasa_prepare_kv(tk, tv, B, Hkv, N, d, scale, ws, wsb, stream, beta=beta, variant=variant)
+    out = np.full(q.shape, np.nan, np.float16)
+    guard = 4096
+    for first, count, row0 in chunks:
+        tq = torch.from_numpy(np.ascontiguousarray(q[:, :, first:first + count])).to(dev)
+        flat = torch.full((tq.numel() + guard,), float("nan"), dtype=torch.float16, device=dev)
+        to = flat[:tq.numel()].view(tq.shape)
+        P.pasa_attn_fwd_chunk(tq, to, B, Hq, Hkv, count, row0, N, d, causal, scale, ws, wsb, stream,
+                              beta=beta, variant=variant)
+        torch.cuda.synchronize()
+        assert bool(torch.isnan(flat[tq.numel():]).all()), "the kernel wrote past the end of the output"
+        out[:, :, first:first + count] = to.cpu().numpy()
+    return out
 
 
 def compare(o, ref):

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     L = P.lib()
     names = _declared_functions()
     assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_workspace", "pasa_prepare_kv",
-            "pasa_attn_fwd_prepared", "pasa_shift_keys", "pasa_optimal_beta", "pasa_invariance_rounded",
+            "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_optimal_beta", "pasa_invariance_rounded",
             "pasa_status_string", "pasa_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
@@ -76,12 +76,14 @@ OK_ARGS = dict(B=1, Hq=4, Hkv=2, N=256, d=64, causal=0, scale=0.125)
 
 def _ex(**over):
     a = dict(OK_ARGS)
-    ptr = dict(q=Q, k=K, v=V, o=O, ws=WS, wsb=1 << 20, beta=-1.0, variant=P.MIXED, shift_tile=128)
+    ptr = dict(q=Q, k=K, v=V, o=O, ws=WS, wsb=1 << 20, beta=-1.0, variant=P.MIXED, shift_tile=128,
+               shift_mode=P.SHIFT_MEAN)
     for key, val in over.items():
         (ptr if key in ptr else a)[key] = val
     return P.pasa_attn_fwd_ex(ptr["q"], ptr["k"], ptr["v"], ptr["o"], a["B"], a["Hq"], a["Hkv"], a["N"], a["d"],
                               a["causal"], a["scale"], ptr["ws"], ptr["wsb"], beta=ptr["beta"],
-                              variant=ptr["variant"], shift_tile=ptr["shift_tile"], check=False)
+                              variant=ptr["variant"], shift_tile=ptr["shift_tile"], shift_mode=ptr["shift_mode"],
+                              check=False)
 
 
 @pytest.mark.parametrize("over,want", [
@@ -92,6 +94,7 @@ def _ex(**over):
     (dict(causal=2), 1), (dict(variant=4), 1), (dict(variant=-1), 1), (dict(beta=1.0), 1), (dict(beta=float("nan")), 1),
     (dict(d=96), 2), (dict(d=256), 2), (dict(N=262144 + 128), 2), (dict(shift_tile=64), 2),
     (dict(ws=0), 4), (dict(ws=WS + 16), 4), (dict(wsb=1024), 4),
+    (dict(shift_mode=2), 1), (dict(shift_mode=-1), 1), (dict(shift_mode=P.SHIFT_MATRIX, N=200), 2),
 ])
 def test_attn_fwd_ex_rejects_bad_arguments(over, want):
     assert _ex(**over) == want
@@ -105,6 +108,17 @@ def test_other_entry_points_reject_bad_arguments():
     assert P.pasa_shift_keys(K, K, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_shift_keys(K, O, 1, 2, 256, 64, 1.0, 0.125, check=False) == 1
     assert P.pasa_shift_keys(K, O, 1, 2, 256, 32, 0.5, 0.125, check=False) == 2
+    assert P.pasa_shift_keys_matrix(K, O, 1, 2, 200, 64, 0.5, 0.125, check=False) == 2    # M is 128 x 128
+    assert P.pasa_shift_keys_matrix(K, O, 1, 2, 256, 64, -0.5, 0.125, check=False) == 1
+    assert P.pasa_prepare_kv(K, V, 1, 2, 200, 64, 0.125, WS, 1 << 20, shift_mode=P.SHIFT_MATRIX, check=False) == 2
+    chunk = dict(B=1, Hq=4, Hkv=2, Nq=100, row0=156, N=256, d=64, causal=1, scale=0.125, workspace=WS,
+                 workspace_bytes=1 << 20, check=False)
+    assert P.pasa_attn_fwd_chunk(0, O, **chunk) == 1
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 0}) == 1
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "row0": -1}) == 1
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 262144 + 1}) == 2
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": 4 * 2 * 256 * 64 - 1}) == 4
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "N": 200, "shift_mode": P.SHIFT_MATRIX}) == 2
     assert P.pasa_prepare_kv(K, V, 1, 2, 256, 64, 0.125, WS, 16, check=False) == 4
     assert P.pasa_prepare_kv(K, 0, 1, 2, 256, 64, 0.125, WS, 1 << 20, check=False) == 1
     assert P.pasa_attn_fwd_prepared(Q, Q, 1, 4, 2, 256, 64, 0, 0.125, WS, 1 << 20, check=False) == 1

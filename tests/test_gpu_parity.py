@@ -16,7 +16,7 @@ import pytest
 import paper_2503_01873_amd as P
 from oracle import pasa_oracle as po
 from workloads import Workload, workload, gen_full, gen_q_head, gen_kv_head
-from gpu_harness import gpu_attn, compare, f32, ORACLE_POLICY, VARIANT_NAME
+from gpu_harness import gpu_attn, gpu_attn_chunks, compare, f32, ORACLE_POLICY, VARIANT_NAME
 
 pytestmark = pytest.mark.gpu
 
@@ -247,6 +247,142 @@ def test_ragged_naive16_matches_oracle():
     o, _ = gpu_attn(q, k, v, False, scale, P.NAIVE16)
     ref = po.fa_bhnd(q, k, v, scale, False, 128, po.PARTIAL16)
     assert compare(o, ref)["maxabs"] <= 2e-3
+
+
+# ------------------------------------------------------------------ shift by the fp16-rounded matrix M (Algorithm 1 as printed)
+
+PAPER_BETA = 0.984497
+
+
+@pytest.mark.parametrize("d,beta,kscale", [(64, PAPER_BETA, 0.125), (128, PAPER_BETA, f32(128 ** -0.5)),
+                                            (128, 0.9375, 1.0), (64, 0.0, f32(64 ** -0.5))])
+def test_shift_keys_matrix_bit_exact(d, beta, kscale):
+    import torch
+    rng = np.random.default_rng(1000 + d)
+    k = (rng.standard_normal((2, 3, 384, d)) * rng.uniform(0.1, 30, (1, 1, 1, d)) + rng.uniform(-80, 80, (2, 3, 1, d))).astype(np.float16)
+    tk = torch.from_numpy(k).cuda()
+    out = torch.empty_like(tk)
+    P.pasa_shift_keys_matrix(tk, out, 2, 3, 384, d, beta, kscale)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = np.stack([[po.shift_keys(k[b, h], beta, kscale, 128, "gemm_m") for h in range(3)] for b in range(2)])
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    if beta == PAPER_BETA:   # the rounded entries do change the result: this is not the mean form in disguise
+        mean_form = np.stack([[po.shift_keys(k[b, h], beta, kscale) for h in range(3)] for b in range(2)])
+        assert (got != mean_form).mean() > 0.05
+
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16])
+def test_matrix_shift_tiny_workload_full_tensor(variant):
+    w = workload(1)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, cnt = gpu_attn(q, k, v, w.causal, scale, variant, counters=True, shift_mode=P.SHIFT_MATRIX)
+    ref = po.pasa_bhnd(q, k, v, scale, w.causal, PAPER_BETA, 128, ORACLE_POLICY[variant], shift="gemm_m")
+    c = compare(o, ref)
+    print(VARIANT_NAME[variant], c)
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    assert c["maxabs"] <= 2e-3
+
+
+@pytest.mark.parametrize("idx,N,over", [(2, 512, dict(Hq=2, Hkv=1)), (3, 640, dict(Hq=7, Hkv=1))])
+def test_matrix_shift_scaled_workloads(idx, N, over):
+    w = _small(idx, N, **over)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, cnt = gpu_attn(q, k, v, w.causal, scale, P.MIXED, counters=True, shift_mode=P.SHIFT_MATRIX)
+    ref = po.pasa_bhnd(q, k, v, scale, w.causal, PAPER_BETA, 128, po.MIXED, shift="gemm_m")
+    gold = po.attention_fp64_bhnd(q, k, v, scale, w.causal)
+    c = compare(o, ref)
+    r_gpu, r_or = po.rmse(o, gold), po.rmse(ref, gold)
+    print(w.name, c, "rmse gpu %.3e oracle %.3e" % (r_gpu, r_or))
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
+    assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
+
+
+# ------------------------------------------------------------------ query chunks: cross-attention, chunked prefill, decoding
+
+def _rows_ref(q, k, v, scale, causal, first, count, row0, policy=po.MIXED):
+    B, Hq = q.shape[:2]
+    g = Hq // k.shape[1]
+    return np.stack([[po.pasa_rows(q[b, h, first:first + count], k[b, h // g], v[b, h // g], scale, causal, BETA, 128,
+                                   policy, row0) for h in range(Hq)] for b in range(B)])
+
+
+@pytest.mark.parametrize("Nq,N,d", [(300, 1000, 64), (1, 640, 128), (513, 128, 128), (64, 77, 64)])
+def test_cross_attention_lengths_differ(Nq, N, d):
+    rng = np.random.default_rng(Nq * 7 + N)
+    q = rng.standard_normal((1, 4, Nq, d)).astype(np.float16)
+    k = (rng.standard_normal((1, 2, N, d)) + 2.5).astype(np.float16)
+    v = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    o = gpu_attn_chunks(q, k, v, False, scale, [(0, Nq, 0)])
+    ref = _rows_ref(q, k, v, scale, False, 0, Nq, 0)
+    c = compare(o, ref)
+    print(Nq, N, d, c)
+    assert np.isfinite(o).all()
+    assert c["maxabs"] <= 2e-3
+
+
+def test_chunked_causal_prefill_equals_one_call():
+    w = _small(3, 1000, Hq=4, Hkv=2)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    whole, _ = gpu_attn(q, k, v, True, scale, P.MIXED)
+    # chunk starts that are multiples of 32 keep every row in the same wavefront slot: bit-identical results
+    parts = gpu_attn_chunks(q, k, v, True, scale, [(0, 256, 0), (256, 448, 256), (704, 296, 704)])
+    assert np.array_equal(whole.view(np.uint16), parts.view(np.uint16))
+    # any other split: each row still follows the same algorithm (summation order of Sbar' may differ)
+    odd = gpu_attn_chunks(q, k, v, True, scale, [(0, 7, 0), (7, 600, 7), (607, 393, 607)])
+    ref = po.pasa_bhnd(q, k, v, scale, True, BETA, 128, po.MIXED)
+    c = compare(odd, ref)
+    print(c)
+    assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
+
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16])
+def test_unaligned_chunks_other_variants(variant):
+    # waves whose rows straddle a key-tile boundary: their first rows see nothing of the later tile
+    w = _small(1, 500)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o = gpu_attn_chunks(q, k, v, True, scale, [(0, 101, 0), (101, 399, 101)], variant=variant)
+    ref = po.pasa_bhnd(q, k, v, scale, True, BETA, 128, ORACLE_POLICY[variant])
+    c = compare(o, ref)
+    print(VARIANT_NAME[variant], c)
+    assert np.isfinite(o).all()
+    assert c["maxabs"] <= 2e-3
+
+
+def test_unaligned_chunks_naive16():
+    rng = np.random.default_rng(61)
+    N, d = 400, 64
+    q = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    k = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    o = gpu_attn_chunks(q, k, v, True, scale, [(0, 50, 0), (50, 350, 50)], variant=P.NAIVE16)
+    ref = po.fa_bhnd(q, k, v, scale, True, 128, po.PARTIAL16)
+    assert compare(o, ref)["maxabs"] <= 2e-3
+
+
+@pytest.mark.parametrize("Nq", [1, 3, 40])
+def test_decoding_against_a_cache(Nq):
+    # the last Nq positions of a sequence of N keys, causal: row0 = N - Nq
+    rng = np.random.default_rng(50 + Nq)
+    N, d = 777, 128
+    q = rng.standard_normal((2, 4, Nq, d)).astype(np.float16)
+    k = (rng.standard_normal((2, 1, N, d)) + 2).astype(np.float16)
+    v = rng.standard_normal((2, 1, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    o = gpu_attn_chunks(q, k, v, True, scale, [(0, Nq, N - Nq)])
+    ref = _rows_ref(q, k, v, scale, True, 0, Nq, N - Nq)
+    assert compare(o, ref)["maxabs"] <= 2e-3
+    # positions past the last key see every key: same as not causal
+    o2 = gpu_attn_chunks(q, k, v, True, scale, [(0, Nq, N + 5)])
+    o3 = gpu_attn_chunks(q, k, v, False, scale, [(0, Nq, 0)])
+    assert compare(o2, o3)["maxabs"] <= 2e-3
 
 
 # ------------------------------------------------------------------ full sizes, sampled, in the benchmark's launch configuration

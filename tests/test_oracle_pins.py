@@ -141,6 +141,37 @@ def test_shift_keys_exact_small_integers_both_modes():
         assert np.array_equal(got, want), mode
 
 
+def test_shift_by_rounded_matrix_is_diagonal_plus_tile_sum():
+    # M16 has one value a on the diagonal and one value b elsewhere, so K^T M16 = (a - b) K + b * (tile sum):
+    # checked against the GEMM written out with python floats, before the final rounding
+    rng = np.random.default_rng(31)
+    T, d, beta, scale = 128, 8, 0.984497, 0.125
+    K = (rng.standard_normal((T, d)) * 2 + 30).astype(np.float16)
+    M16 = po.fl(po.shift_matrix(beta, T, 1.0 / scale), "f16")
+    a, b = M16[0, 0], M16[0, 1]
+    assert np.all(M16[~np.eye(T, dtype=bool)] == b) and np.all(np.diag(M16) == a)
+    assert a == np.float16(scale * (1 - beta / T)) and b == np.float16(-scale * beta / T)
+    got = po.shift_keys(K, beta, scale, T, "gemm_m", fmt="f64")
+    K64 = K.astype(np.float64)
+    want = (a - b) * K64 + b * K64.sum(0, keepdims=True)
+    assert np.abs(got - want).max() < 1e-12
+    brute = np.array([[sum(float(M16[p, q]) * float(K[p, c]) for p in range(T)) for c in range(d)] for q in range(T)])
+    assert np.abs(got - brute).max() < 1e-12
+
+
+def test_causal_rows_past_the_last_key_see_all_keys():
+    rng = np.random.default_rng(32)
+    N, d = 200, 16
+    Q = rng.standard_normal((5, d)).astype(np.float16)
+    K = (rng.standard_normal((N, d)) + 1).astype(np.float16)
+    V = rng.standard_normal((N, d)).astype(np.float16)
+    got = po.pasa_rows(Q, K, V, 0.25, True, 0.5, 128, po.EXACT64, row0=N - 2)   # positions N-2 .. N+2
+    gold = po.attention_fp64(Q, K, V, 0.25, True, N - 2)
+    assert po.rmse(got, gold) < 2e-3
+    full = po.attention_fp64(Q[2:], K, V, 0.25, False)
+    assert np.allclose(gold[2:], full, atol=1e-12)
+
+
 def test_shift_keys_modes_agree_to_rounding():
     rng = np.random.default_rng(3)
     K = (rng.standard_normal((256, 64)) * 3 + 40).astype(np.float16)
