@@ -11,7 +11,7 @@
  * N need not be a multiple of 128: a ragged last tile uses its own key count as the divisor of the tile
  * mean and of the pseudo-average, which keeps Eq. (14) valid for it (the paper does not state this case).
  *
- * Layouts.  q, o: [B, Hq, N, d];  k, v: [B, Hkv, N, d].  IEEE fp16, row-major, contiguous, DEVICE
+ * Layouts.  q, o: [B, Hq, N, d];  k, v: [B, Hkv, N, d].  IEEE fp16 (or bf16, see pasa_io_dtype), row-major, contiguous, DEVICE
  * pointers, 16-byte aligned.  Query head h reads KV head h / (Hq / Hkv) (grouped-query attention; the
  * paper does not discuss it).  causal != 0: key n is visible to query r iff n <= r.
  *
@@ -62,6 +62,11 @@ typedef enum {
                               is the same contraction.  Needs N % 128 == 0. */
 } pasa_shift_mode;
 
+/* Element type of q, k, v and o.  The method computes in fp16: bf16 inputs are converted to fp16 as they are loaded
+ * (round to nearest even; magnitudes beyond 65504 become infinities), as the paper prescribes for BF16 inputs, and
+ * the output is rounded to bf16 when it is stored. */
+typedef enum { PASA_IO_F16 = 0, PASA_IO_BF16 = 1 } pasa_io_dtype;
+
 typedef struct {
     float beta;        /* shift fraction of Eq. (10).  < 0: library default -- by mean 63.5/64.5 (invariance beta/(1-beta) =
                           63.5, the fp16 value of the invariance of the paper's adopted beta), by matrix the paper's
@@ -72,6 +77,8 @@ typedef struct {
                                         exceeds 65504 where they would be stored as fp16.  NULL: not counted. */
     unsigned long long* nonfinite_o; /* optional DEVICE counter (caller zeroes it): inf/NaN entries written to o. */
     int shift_mode;    /* a pasa_shift_mode */
+    int io_dtype;      /* a pasa_io_dtype; applies to q, k, v, o of the call it is passed to (the workspace is always
+                          fp16, so pasa_prepare_kv and the calls that use its workspace may differ in it) */
 } pasa_opts;
 
 /* Default configuration: PASA_MIXED, default beta.  Allocates and frees its workspace in stream order
@@ -85,7 +92,7 @@ size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
  * at least pasa_attn_fwd_workspace() bytes; contents on return are unspecified).  opts == NULL means
- * {beta = -1, PASA_MIXED, 128, NULL, NULL, PASA_SHIFT_MEAN}.  Performs no allocation. */
+ * {beta = -1, PASA_MIXED, 128, NULL, NULL, PASA_SHIFT_MEAN, PASA_IO_F16}.  Performs no allocation. */
 int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
                      int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                      const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);

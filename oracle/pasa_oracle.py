@@ -61,8 +61,21 @@ def fl(x, fmt: str) -> np.ndarray:
     x = np.asarray(x, dtype=np.float64)
     if fmt == "f64":
         return x
+    if fmt == "bf16":
+        return _round_bf16(x)
     with np.errstate(over="ignore", invalid="ignore"):
         return x.astype(_NP[fmt]).astype(np.float64)
+
+
+def _round_bf16(x: np.ndarray) -> np.ndarray:
+    """bfloat16 (Table 1: 8 exponent bits, 8 significand bits with the hidden one) from fp64, one rounding."""
+    x = np.asarray(x, dtype=np.float64)
+    with np.errstate(over="ignore", invalid="ignore"):
+        m, e = np.frexp(x)                                  # x = m * 2^e, 0.5 <= |m| < 1
+        lsb = np.maximum(e - 8, -133)                       # weight of the last kept bit; -133: subnormal spacing
+        r = np.ldexp(np.rint(np.ldexp(x, -lsb)), lsb)       # rint: ties to even
+        r = np.where(np.abs(r) >= 2.0 ** 128, np.copysign(np.inf, x), r)
+    return np.where(np.isfinite(x), r, x)
 
 
 @dataclass(frozen=True)
@@ -179,9 +192,20 @@ def attention_fp64(Q, K, V, scale: float, causal: bool, row0: int = 0) -> np.nda
 # Algorithm 1, step by step
 # ----------------------------------------------------------------------------------------------
 
+def from_bf16(x) -> np.ndarray:
+    """The paper's rule for BF16 inputs: convert them to FP16 and run the method on that.  x holds bf16 values
+    (in any wider numpy type); the result is the fp16 array the method then sees."""
+    with np.errstate(over="ignore"):
+        return np.asarray(x, np.float64).astype(np.float16)
+
+
 def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
-              policy: Policy = MIXED, row0: int = 0, shift: str = "mean", info: dict | None = None):
+              policy: Policy = MIXED, row0: int = 0, shift: str = "mean", info: dict | None = None,
+              out_fmt: str = "f16"):
     """Algorithm 1 for query rows row0 .. row0+R-1 of one head.  Q [R,d], K,V [N,d] fp16 -> fp16 [R,d].
+
+    out_fmt "bf16": the quotient O / l is rounded to the precision O is kept in, then to bf16, and returned as
+    float32 values (numpy has no bf16 type).
 
     Rows are independent: all state (F, m, l, O) is per query row.  If `info` is a dict it receives
     max |S'| over finite entries, the number of non-finite S' entries and of S' entries seen.
@@ -239,7 +263,10 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
             O[a] = fl(fl(ec[:, None] * Ot, pO) + fl(ep[:, None] * O[a], pO), pO)
             m[a] = mnew
             F[a] = Fnew
-        out = (O / l[:, None]).astype(np.float16)
+        if out_fmt == "bf16":
+            out = fl(fl(O / l[:, None], pO), "bf16").astype(np.float32)
+        else:
+            out = (O / l[:, None]).astype(np.float16)
     if info is not None:
         info.update(smax=smax, s_nonfinite=s_nonfinite, s_seen=s_seen)
     return out

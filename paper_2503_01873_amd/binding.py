@@ -11,6 +11,7 @@ import os
 
 MIXED, STRICT16, NAIVE16, S16 = 0, 1, 2, 3
 SHIFT_MEAN, SHIFT_MATRIX = 0, 1
+IO_F16, IO_BF16 = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("PASA_LIB") or os.path.join(_PKG, "libpasa.so")
@@ -31,6 +32,7 @@ class pasa_opts(ctypes.Structure):
         ("overflow_s", ctypes.c_void_p),
         ("nonfinite_o", ctypes.c_void_p),
         ("shift_mode", ctypes.c_int),
+        ("io_dtype", ctypes.c_int),
     ]
 
 
@@ -127,8 +129,9 @@ def pasa_attn_fwd(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, stream=None, chec
 
 def pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, workspace, workspace_bytes, stream=None,
                      beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
-                     shift_mode=SHIFT_MEAN, opts_null=False, check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode))
+                     shift_mode=SHIFT_MEAN, io_dtype=IO_F16, opts_null=False, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode),
+                     int(io_dtype))
     st = lib().pasa_attn_fwd_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, Hq, Hkv, N, d, int(causal), float(scale),
                                 None if opts_null else ctypes.byref(opts), _ptr(workspace), int(workspace_bytes),
                                 _stream(stream))
@@ -136,8 +139,8 @@ def pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, workspace, wor
 
 
 def pasa_prepare_kv(k, v, B, Hkv, N, d, scale, workspace, workspace_bytes, stream=None, beta=-1.0, variant=MIXED,
-                    shift_tile=128, shift_mode=SHIFT_MEAN, check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), None, None, int(shift_mode))
+                    shift_tile=128, shift_mode=SHIFT_MEAN, io_dtype=IO_F16, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), None, None, int(shift_mode), int(io_dtype))
     st = lib().pasa_prepare_kv(_ptr(k), _ptr(v), B, Hkv, N, d, float(scale), ctypes.byref(opts), _ptr(workspace),
                                int(workspace_bytes), _stream(stream))
     return _check(st, "pasa_prepare_kv", check)
@@ -145,8 +148,9 @@ def pasa_prepare_kv(k, v, B, Hkv, N, d, scale, workspace, workspace_bytes, strea
 
 def pasa_attn_fwd_prepared(q, o, B, Hq, Hkv, N, d, causal, scale, workspace, workspace_bytes, stream=None,
                            beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
-                           shift_mode=SHIFT_MEAN, check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode))
+                           shift_mode=SHIFT_MEAN, io_dtype=IO_F16, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode),
+                     int(io_dtype))
     st = lib().pasa_attn_fwd_prepared(_ptr(q), _ptr(o), B, Hq, Hkv, N, d, int(causal), float(scale),
                                       ctypes.byref(opts), _ptr(workspace), int(workspace_bytes), _stream(stream))
     return _check(st, "pasa_attn_fwd_prepared", check)
@@ -165,8 +169,9 @@ def pasa_shift_keys_matrix(k, kprime, B, Hkv, N, d, beta, kscale, stream=None, c
 
 def pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, workspace, workspace_bytes, stream=None,
                         beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
-                        shift_mode=SHIFT_MEAN, check=True) -> int:
-    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode))
+                        shift_mode=SHIFT_MEAN, io_dtype=IO_F16, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode),
+                     int(io_dtype))
     st = lib().pasa_attn_fwd_chunk(_ptr(q), _ptr(o), B, Hq, Hkv, Nq, row0, N, d, int(causal), float(scale),
                                    ctypes.byref(opts), _ptr(workspace), int(workspace_bytes), _stream(stream))
     return _check(st, "pasa_attn_fwd_chunk", check)

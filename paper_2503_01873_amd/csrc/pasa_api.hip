@@ -122,7 +122,7 @@ int shift_keys_common(const void* k, void* kprime, int B, int Hkv, int N, int d,
         if (N % kShiftTile != 0) return PASA_EUNSUPPORTED;   // M is a full 128 x 128 matrix
         rounded_shift_matrix(beta, kscale, &c1, &c2);
     }
-    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, matrix_mode,
+    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, matrix_mode, 0,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
@@ -150,6 +150,7 @@ struct Params {
     double beta;      // shift fraction used by the pre-processing kernel (matrix mode: a - b)
     double kscale;    // factor folded into K' (matrix mode: b)
     int matrix_mode;  // K' by the fp16-rounded shifting matrix instead of by the tile mean
+    int io_bf16;      // q, k, v, o hold bf16
     float inva;       // beta/(1-beta) rounded to the statistics precision
     unsigned long long* overflow_s;
     unsigned long long* nonfinite_o;
@@ -158,10 +159,11 @@ struct Params {
 int resolve(const pasa_opts* opts, float scale, Params* out)
 {
     if (!isfinite(scale) || !(scale > 0.f)) return PASA_EINVAL;
-    pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr, PASA_SHIFT_MEAN};
+    pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr, PASA_SHIFT_MEAN, PASA_IO_F16};
     if (opts != nullptr) op = *opts;
     if (op.variant < PASA_MIXED || op.variant > PASA_S16) return PASA_EINVAL;
     if (op.shift_mode != PASA_SHIFT_MEAN && op.shift_mode != PASA_SHIFT_MATRIX) return PASA_EINVAL;
+    if (op.io_dtype != PASA_IO_F16 && op.io_dtype != PASA_IO_BF16) return PASA_EINVAL;
     if (op.shift_tile != 0 && op.shift_tile != kShiftTile) return PASA_EUNSUPPORTED;
     if (!(op.beta < 1.f)) return PASA_EINVAL;              // also rejects NaN
     // beta and the invariance beta/(1-beta) in fp64.  Default by mean: the invariance is exactly 63.5.  Default by
@@ -177,6 +179,7 @@ int resolve(const pasa_opts* opts, float scale, Params* out)
     out->variant = op.variant;
     out->beta = beta;
     out->kscale = kscale;
+    out->io_bf16 = op.io_dtype == PASA_IO_BF16;
     out->matrix_mode = op.shift_mode == PASA_SHIFT_MATRIX;
     if (out->matrix_mode) rounded_shift_matrix(beta, kscale, &out->beta, &out->kscale);
     out->inva = op.variant == PASA_STRICT16 ? (float)round_to_format(inva_d, 11, -14, 15) : (float)inva_d;
@@ -206,7 +209,7 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
     const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, pr.matrix_mode,
-                                          static_cast<hipStream_t>(stream));
+                                          pr.io_bf16, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
 
@@ -238,6 +241,7 @@ int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, 
     p.Nq = Nq; p.row0 = causal ? row0 : 0;
     p.causal = causal;
     p.variant = pr.variant;
+    p.io_bf16 = pr.io_bf16;
     p.inva = pr.inva;
     p.scale = scale;
     p.overflow_s = pr.overflow_s;

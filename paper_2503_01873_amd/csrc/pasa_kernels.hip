@@ -34,6 +34,32 @@
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+// bf16 inputs are converted to fp16 as they are loaded (the paper's remark on BF16 inputs): round to nearest even,
+// values beyond the fp16 range become infinities.
+__device__ inline h8 bf16x8_to_h8(u16x8 raw)
+{
+    h8 out;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out[e] = (_Float16)__uint_as_float((unsigned)raw[e] << 16);
+    return out;
+}
+
+__device__ inline h8 load_h8(const _Float16* p, int is_bf16)
+{
+    if (is_bf16) return bf16x8_to_h8(*reinterpret_cast<const u16x8*>(p));
+    return *reinterpret_cast<const h8*>(p);
+}
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN
+__device__ inline unsigned short f32_to_bf16_rn(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 
@@ -68,7 +94,7 @@ template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
                                                     _Float16* __restrict__ wsout,
                                                     _Float16* __restrict__ plain_out, int N, int ntile,
-                                                    double beta, double kscale, int matrix_mode)
+                                                    double beta, double kscale, int matrix_mode, int in_bf16)
 {
     constexpr int CH = D / 8;            // 16-byte chunks per key
     constexpr int KL = 256 / CH;         // key lanes
@@ -90,7 +116,7 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
         const int n = kl + KL * i;
-        kv[i] = n < nvalid ? *reinterpret_cast<const h8*>(ksrc + n * D + 8 * c8) : (h8)(_Float16)0;
+        kv[i] = n < nvalid ? load_h8(ksrc + n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s[e] += (double)kv[i][e];   // exact: fp16 values, at most 128 terms
     }
@@ -103,7 +129,7 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
         for (int i = 0; i < KPT; ++i) {
             const int n = kl + KL * i;
             *reinterpret_cast<h8*>(&vs[n][8 * c8]) =
-                n < nvalid ? *reinterpret_cast<const h8*>(vsrc + n * D + 8 * c8) : (h8)(_Float16)0;
+                n < nvalid ? load_h8(vsrc + n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
         }
     }
     __syncthreads();
@@ -235,7 +261,7 @@ __device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
-              int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale,
+              int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale, int io_bf16,
               unsigned long long* ovf_s, unsigned long long* nonfinite_o)
 {
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
@@ -321,7 +347,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     h8 Qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
-        Qf[ks] = row_valid ? *reinterpret_cast<const h8*>(qbase + (size_t)row * D + 16 * ks + 8 * lh) : (h8)(_Float16)0;
+        Qf[ks] = row_valid ? load_h8(qbase + (size_t)row * D + 16 * ks + 8 * lh, io_bf16) : (h8)(_Float16)0;
 
     // per-row state (one query row per lane; both halves of the wave hold copies)
     float F = 0.f, m = NAIVE ? -__builtin_inff() : 0.f, l = 0.f;   // STRICT: always fp16-representable values
@@ -747,22 +773,26 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
                 h4 out;
+                u16x4 outb;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int i = 4 * gq + r;
-                    _Float16 val;
-                    if (!STRICT) {
-                        val = (_Float16)(O[cb][i] * oscale);
-                    } else {
-                        val = (_Float16)(O16[cb][i >> 1][i & 1] / (_Float16)l);
-                    }
+                    // fp32 variants: the fp32 quotient is rounded once, to the output type; STRICT16: the fp16
+                    // quotient of Algorithm 1's last line, converted when the output is bf16
+                    const float v32 = STRICT ? (float)(_Float16)(O16[cb][i >> 1][i & 1] / (_Float16)l) : O[cb][i] * oscale;
+                    const _Float16 val = (_Float16)v32;
+                    outb[r] = f32_to_bf16_rn(v32);
                     if (INSTR && row_valid) {
-                        const float fv = (float)val;
+                        const float fv = io_bf16 ? __uint_as_float((unsigned)outb[r] << 16) : (float)val;
                         n_bad += (fv != fv || __builtin_fabsf(fv) == __builtin_inff()) ? 1u : 0u;
                     }
                     out[r] = val;
                 }
-                if (row_valid) *reinterpret_cast<h4*>(obase + (size_t)row * D + 32 * cb + 8 * gq + 4 * lh) = out;
+                _Float16* dst = obase + (size_t)row * D + 32 * cb + 8 * gq + 4 * lh;
+                if (row_valid) {
+                    if (io_bf16) *reinterpret_cast<u16x4*>(dst) = outb;
+                    else *reinterpret_cast<h4*>(dst) = out;
+                }
             }
     }
     if (INSTR) {
@@ -783,7 +813,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
                                        LDS_BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
-                       (_Float16*)p.o, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.overflow_s, p.nonfinite_o);
+                       (_Float16*)p.o, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s, p.nonfinite_o);
     return hipGetLastError();
 }
 
@@ -810,17 +840,17 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 }  // namespace
 
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
-                            int B, int Hkv, int N, int d, double beta, double kscale, int matrix_mode,
+                            int B, int Hkv, int N, int d, double beta, double kscale, int matrix_mode, int in_bf16,
                             hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
     const dim3 grid((unsigned)((size_t)B * Hkv * ntile));
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode);
+                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode, in_bf16);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode);
+                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode, in_bf16);
     return hipGetLastError();
 }
 

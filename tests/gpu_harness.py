@@ -16,13 +16,24 @@ def f32(x: float) -> float:
     return float(np.float32(x))
 
 
+def bf16_bits(x32):
+    """float32 array holding bf16-representable values -> their 16-bit patterns (input plumbing only)."""
+    x32 = np.ascontiguousarray(x32, np.float32)
+    u = x32.view(np.uint32)
+    assert not (u & 0xFFFF).any(), "not bf16 values"
+    return (u >> 16).astype(np.uint16)
+
+
 def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False, entry="ex",
-             shift_mode=P.SHIFT_MEAN):
-    """Run the HIP path on numpy fp16 inputs [B,H,N,d]; returns (o fp16 numpy, counters or None)."""
+             shift_mode=P.SHIFT_MEAN, bf16=False):
+    """Run the HIP path on numpy fp16 inputs [B,H,N,d]; returns (o fp16 numpy, counters or None).
+    bf16=True: inputs are float32 arrays of bf16 values, passed to the device as bf16; o comes back as float32."""
     import torch
     dev = torch.device("cuda:0")
     B, Hq, N, d = q.shape
     Hkv = k.shape[1]
+    if bf16:   # same 2-byte element size: the fp16-typed torch buffers below only carry the bits
+        q, k, v = (bf16_bits(x).view(np.float16) for x in (q, k, v))
     tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (q, k, v))
     guard = 4096                        # sentinel elements after the output: nothing may write past its end
     flat = torch.full((tq.numel() + guard,), float("nan"), dtype=torch.float16, device=dev)
@@ -34,7 +45,7 @@ def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False,
     else:
         wsb = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
         ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
-        kw = dict(beta=beta, variant=variant, shift_mode=shift_mode)
+        kw = dict(beta=beta, variant=variant, shift_mode=shift_mode, io_dtype=P.IO_BF16 if bf16 else P.IO_F16)
         if entry == "ex":
             P.pasa_attn_fwd_ex(tq, tk, tv, to, B, Hq, Hkv, N, d, causal, scale, ws, wsb, stream,
                                overflow_s=cnt[0:1] if counters else None,
@@ -46,7 +57,10 @@ def gpu_attn(q, k, v, causal, scale, variant=P.MIXED, beta=-1.0, counters=False,
             raise ValueError(entry)
     torch.cuda.synchronize()
     assert bool(torch.isnan(flat[tq.numel():]).all()), "the kernel wrote past the end of the output"
-    return to.cpu().numpy(), (cnt.cpu().numpy() if counters else None)
+    o = to.cpu().numpy()
+    if bf16:
+        o = (o.view(np.uint16).astype(np.uint32) << 16).view(np.float32)
+    return o, (cnt.cpu().numpy() if counters else None)
 
 
 def gpu_attn_chunks(q, k, v, causal, scale, chunks, variant=P.MIXED, beta=-1.0):

@@ -55,6 +55,7 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
         assert P.pasa_invariance_rounded(b0, 128, 0) == pytest.approx(po.invariance_rounded(b0, 128, "f16"), rel=1e-12)
     # bf16 (8 significand bits): 1 - beta/n rounds to 1, so a = 1 + b and the solution is a fixed point
     b = P.pasa_optimal_beta(1 - 2.0 ** -4, 128, 1)
+    assert b == pytest.approx(po.optimal_beta(1 - 2.0 ** -4, 128, "bf16"), rel=1e-12)
     assert P.pasa_invariance_rounded(b, 128, 1) == pytest.approx(b / (1 - b), rel=1e-7)
     assert math.isnan(P.pasa_optimal_beta(1.5, 128, 0))
     assert math.isnan(P.pasa_optimal_beta(0.9, 0, 0))
@@ -77,13 +78,13 @@ OK_ARGS = dict(B=1, Hq=4, Hkv=2, N=256, d=64, causal=0, scale=0.125)
 def _ex(**over):
     a = dict(OK_ARGS)
     ptr = dict(q=Q, k=K, v=V, o=O, ws=WS, wsb=1 << 20, beta=-1.0, variant=P.MIXED, shift_tile=128,
-               shift_mode=P.SHIFT_MEAN)
+               shift_mode=P.SHIFT_MEAN, io_dtype=P.IO_F16)
     for key, val in over.items():
         (ptr if key in ptr else a)[key] = val
     return P.pasa_attn_fwd_ex(ptr["q"], ptr["k"], ptr["v"], ptr["o"], a["B"], a["Hq"], a["Hkv"], a["N"], a["d"],
                               a["causal"], a["scale"], ptr["ws"], ptr["wsb"], beta=ptr["beta"],
                               variant=ptr["variant"], shift_tile=ptr["shift_tile"], shift_mode=ptr["shift_mode"],
-                              check=False)
+                              io_dtype=ptr["io_dtype"], check=False)
 
 
 @pytest.mark.parametrize("over,want", [
@@ -95,6 +96,7 @@ def _ex(**over):
     (dict(d=96), 2), (dict(d=256), 2), (dict(N=262144 + 128), 2), (dict(shift_tile=64), 2),
     (dict(ws=0), 4), (dict(ws=WS + 16), 4), (dict(wsb=1024), 4),
     (dict(shift_mode=2), 1), (dict(shift_mode=-1), 1), (dict(shift_mode=P.SHIFT_MATRIX, N=200), 2),
+    (dict(io_dtype=2), 1), (dict(io_dtype=-1), 1),
 ])
 def test_attn_fwd_ex_rejects_bad_arguments(over, want):
     assert _ex(**over) == want

@@ -301,6 +301,55 @@ def test_matrix_shift_scaled_workloads(idx, N, over):
     assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
 
 
+# ------------------------------------------------------------------ bf16 inputs and outputs
+
+def _bf16_case(idx, N, **over):
+    w = _small(idx, N, **over)
+    q, k, v = gen_full(w)
+    # the workload's values rounded to bf16 (generator side: no arithmetic of the method)
+    return w, tuple(po.fl(x.astype(np.float64), "bf16").astype(np.float32) for x in (q, k, v))
+
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16])
+@pytest.mark.parametrize("idx,N,over", [(1, 512, {}), (3, 600, dict(Hq=7, Hkv=1))])
+def test_bf16_io(idx, N, over, variant):
+    w, (q, k, v) = _bf16_case(idx, N, **over)
+    scale = f32(w.scale)
+    o, cnt = gpu_attn(q, k, v, w.causal, scale, variant, counters=True, bf16=True)
+    qh, kh, vh = po.from_bf16(q), po.from_bf16(k), po.from_bf16(v)
+    g = w.Hq // w.Hkv
+    ref = np.stack([[po.pasa_rows(qh[b, h], kh[b, h // g], vh[b, h // g], scale, w.causal, BETA, 128,
+                                  ORACLE_POLICY[variant], out_fmt="bf16") for h in range(w.Hq)] for b in range(w.B)])
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    # compare in units of the reference's bf16 spacing: the stored values are 8-bit significands
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 2.0 ** -126))) - 7)
+    steps = np.abs(o.astype(np.float64) - ref) / ulp
+    c = compare(o, ref)
+    print(w.name, VARIANT_NAME[variant], c, "max ulps %.1f, >1 ulp: %.2e" % (steps.max(), (steps > 1).mean()))
+    # one bf16 step of an output below 1 is up to 3.9e-3; outputs near zero differ by many of their own (tiny) steps
+    if idx == 1:
+        assert c["maxabs"] <= 4e-3
+    else:
+        assert c["p999"] <= 4e-3 and c["maxabs"] <= 1.6e-2
+    assert (o == ref).mean() > (0.9 if variant == P.MIXED else 0.6)
+
+
+def test_bf16_input_beyond_fp16_range_becomes_infinite_like_the_oracle():
+    rng = np.random.default_rng(77)
+    N, d = 256, 64
+    q = po.fl(rng.standard_normal((1, 1, N, d)), "bf16").astype(np.float32)
+    k = po.fl(rng.standard_normal((1, 1, N, d)), "bf16").astype(np.float32)
+    v = po.fl(rng.standard_normal((1, 1, N, d)), "bf16").astype(np.float32)
+    v[0, 0, 3, 5] = 131072.0         # a bf16 value: +inf once converted to fp16
+    o, cnt = gpu_attn(q, k, v, False, 0.125, P.MIXED, counters=True, bf16=True)
+    ref = po.pasa_rows(po.from_bf16(q[0, 0]), po.from_bf16(k[0, 0]), po.from_bf16(v[0, 0]), 0.125, False, BETA, 128,
+                       po.MIXED, out_fmt="bf16")
+    assert np.isinf(ref[:, 5]).all() and np.isinf(o[0, 0, :, 5]).all()
+    keep = np.arange(d) != 5
+    assert np.isfinite(o[0, 0][:, keep]).all()
+    assert cnt[1] == N
+
+
 # ------------------------------------------------------------------ query chunks: cross-attention, chunked prefill, decoding
 
 def _rows_ref(q, k, v, scale, causal, first, count, row0, policy=po.MIXED):

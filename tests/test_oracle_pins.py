@@ -92,7 +92,7 @@ def test_table3_invariance(golden):
             assert round(b, digits) == float(bopt)
 
 
-def test_optimal_beta_bf16_is_a_fixed_point():
+def test_optimal_beta_exact_solution_and_other_sizes():
     b = po.optimal_beta(1 - 2.0 ** -4, 128, "f16")
     assert b == 0.9375
     # generic property for another size: the solution satisfies the condition it solves
@@ -427,3 +427,51 @@ def test_rmse_ordering_nonzero_mean():
         assert e32 < epasa < e16, (pol, e32, epasa, e16)
     estrict = po.rmse(po.pasa_rows(Q, K, V, scale, False, po.default_beta(), 128, po.STRICT16), gold)
     assert estrict < 0.02
+
+
+# ------------------------------------------------------------------ bf16 (Table 1; the remark on BF16 inputs)
+
+def test_bf16_rounding_against_torch_and_hand_cases():
+    import torch
+    # every bf16 bit pattern is a fixed point
+    bits = (np.arange(65536, dtype=np.uint32) << 16).view(np.float32)
+    fin = np.isfinite(bits)
+    assert np.array_equal(po.fl(bits[fin].astype(np.float64), "bf16"), bits[fin].astype(np.float64))
+    # float32 values (exact in fp64): torch rounds float32 -> bfloat16 to nearest even
+    rng = np.random.default_rng(41)
+    x = np.concatenate([rng.standard_normal(20000) * 10.0 ** rng.integers(-42, 38, 20000),
+                        rng.uniform(-4, 4, 20000)]).astype(np.float32)
+    # ties: odd multiples of half a bf16 ulp
+    ties = ((np.arange(1, 4001, 2, dtype=np.float64) / 256.0 + 1.0) / 2).astype(np.float32)
+    x = np.concatenate([x, ties, -ties, np.float32([3.3895314e38, 3.4e38, 1e-40, 9.2e-41, 4.6e-41, 0.0])])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(po.fl(x.astype(np.float64), "bf16"), want)
+    # one rounding, not two: via fp32 this value would fall on a tie and go down to 1.0
+    assert po.fl(1 + 2.0 ** -8 + 2.0 ** -30, "bf16") == 1 + 2.0 ** -7
+    assert po.fl(1 + 2.0 ** -8, "bf16") == 1.0 and po.fl(1 + 3 * 2.0 ** -8, "bf16") == 1 + 2.0 ** -6
+    assert po.fl(2.0 ** 128, "bf16") == np.inf and po.fl(-1e39, "bf16") == -np.inf
+
+
+def test_optimal_beta_in_bf16_satisfies_its_condition():
+    b = po.optimal_beta(1 - 2.0 ** -4, 128, "bf16")
+    assert po.invariance_rounded(b, 128, "bf16") == pytest.approx(b / (1 - b), rel=1e-7)
+
+
+def test_bf16_inputs_are_converted_to_fp16_then_the_method_runs():
+    rng = np.random.default_rng(42)
+    N, d = 300, 16
+    mk = lambda *sh: po.fl(rng.standard_normal(sh) * 2 + 1, "bf16")
+    Q, K, V = mk(40, d), mk(N, d), mk(N, d)
+    K[5, 3] = 70000.0                                   # a bf16 value beyond fp16: becomes +inf on conversion
+    assert np.isinf(po.from_bf16(K)[5, 3]) and po.from_bf16(K).dtype == np.float16
+    K[5, 3] = 1.0
+    Qh, Kh, Vh = po.from_bf16(Q), po.from_bf16(K), po.from_bf16(V)
+    assert np.array_equal(Qh.astype(np.float64), Q)     # 8 significant bits in the fp16 range: exact
+    gold = po.attention_fp64(Qh, Kh, Vh, 0.25, True, 260)
+    got = po.pasa_rows(Qh, Kh, Vh, 0.25, True, 0.9375, 128, po.EXACT64, 260, out_fmt="bf16")
+    assert got.dtype == np.float32 and np.array_equal(po.fl(got, "bf16"), got)
+    assert np.abs(got - gold).max() <= 2.0 ** -8 * np.abs(gold).max()
+    # output rounding only: the f16 and bf16 outputs come from the same quotient
+    got16 = po.pasa_rows(Qh, Kh, Vh, 0.25, True, 0.9375, 128, po.MIXED, 260)
+    gotb = po.pasa_rows(Qh, Kh, Vh, 0.25, True, 0.9375, 128, po.MIXED, 260, out_fmt="bf16")
+    assert np.abs(gotb - got16.astype(np.float64)).max() <= 2.0 ** -8 * np.abs(got16.astype(np.float64)).max()
