@@ -447,6 +447,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // Both GEMMs run as one chain of MFMAs per accumulator block (the block index is the slow one), with the LDS
     // fragments PF instructions ahead.  hook(n) is vector work of the same wave placed behind MFMA n; it is issued
     // while that MFMA executes.
+    // The code generator otherwise sinks a hook's arithmetic into the later block that uses its result, away from the
+    // MFMA it was meant to run behind; an empty volatile asm that takes and returns the values keeps it in place.
+#define PASA_PIN2(a, b) asm volatile("" : "+v"(a), "+v"(b))
     constexpr int PF = 4;
     constexpr int NM1 = 4 * KS;      // MFMAs of the first GEMM:  n = kb * KS + ks
     constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM: n = cb * 8 + kk
@@ -521,8 +524,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 gemm2(j - 1, [&](int n) {
                     const int cb = n / 8, kk = n % 8;
                     if (cb + 1 < CB) {
-                        O[cb + 1][2 * kk] *= g_pend;
-                        O[cb + 1][2 * kk + 1] *= g_pend;
+                        float x0 = O[cb + 1][2 * kk] * g_pend, x1 = O[cb + 1][2 * kk + 1] * g_pend;
+                        PASA_PIN2(x0, x1);
+                        O[cb + 1][2 * kk] = x0;
+                        O[cb + 1][2 * kk + 1] = x1;
                     }
                 });
             }
@@ -561,6 +566,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         sacc += S[kb][i];
                         macc = __builtin_fmaxf(macc, S[kb][i]);
                     }
+                    PASA_PIN2(sacc, macc);
                     ps[kb] = sacc;
                     pm[kb] = macc;
                 });
