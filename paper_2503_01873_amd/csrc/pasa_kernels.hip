@@ -226,14 +226,16 @@ __device__ inline float add_pair(h2 v, float acc)
     return __builtin_amdgcn_fdot2(v, one, acc, false);
 }
 
-// One wave-wide direct global -> LDS copy of 1 KiB: lane i moves 16 bytes from gsrc + 16*i to ldst + 16*i.
-// ldst must be wave-uniform (it travels in M0).
+// One wave-wide direct global -> LDS copy of 1 KiB: lane i moves 16 bytes from byte soff + 16*i of the buffer to
+// ldst + 16*i.  soff and ldst must be wave-uniform (ldst travels in M0).
 // OFF is an immediate added to both addresses, so a wave's consecutive pieces share one M0 value.
+// The buffer form (buffer_load ... lds) is used rather than global_load_lds: the compiler treats the latter as a flat
+// access that may touch LDS and from then on drains the LDS counter to zero before every use of an LDS fragment,
+// which defeats the fragment prefetch of the GEMM loops.  A buffer load out of range returns zeros instead of faulting.
 template <int OFF>
-__device__ inline void copy_1k_to_lds(const char* gsrc, char* ldst, int lane)
+__device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char* ldst, int lane)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc + lane * 16),
-                                     (__attribute__((address_space(3))) void*)ldst, 16, OFF, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (__attribute__((address_space(3))) void*)ldst, 16, lane * 16, soff, OFF, 0);
 }
 
 #define PASA_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -334,12 +336,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     const _Float16* qbase = q + ((size_t)(b * Hq + hq) * Nq) * D;
     const char* wsbase = ws + ((size_t)(b * Hkv + hk) * ntile) * TILE_BYTES;
+    // raw buffer over this (batch, KV head)'s tiles: at most 2048 tiles of 64 KiB, so every offset fits 32 bits
+    const __amdgpu_buffer_rsrc_t wsbuf =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wsbase), 0, ntile * TILE_BYTES, 0x00020000);
 
     auto issue_k = [&](int j) {
-        const char* src = wsbase + (size_t)j * TILE_BYTES;
+        const int src = j * TILE_BYTES;
         char* dst = smem + (j & 1) * KT_BYTES;
 #pragma unroll
-        for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
+        for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(wsbuf, src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
     };
     issue_k(0);
 
@@ -396,11 +401,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         const int jl = sg >> 1;
         if (piece < CPW) {
             if (jl + 1 < J_wg)
-                copy_1k_to_lds<(piece % CPW) * 1024>(wsbase + (size_t)(jl + 1) * TILE_BYTES + wave * (CPW * 1024),
+                copy_1k_to_lds<(piece % CPW) * 1024>(wsbuf, (jl + 1) * TILE_BYTES + wave * (CPW * 1024),
                                                      smem + ((jl + 1) & 1) * KT_BYTES + wave * (CPW * 1024), lane);
         } else {
             if (jl < J_wg)
-                copy_1k_to_lds<(piece % CPW) * 1024>(wsbase + (size_t)jl * TILE_BYTES + KT_BYTES + wave * (CPW * 1024),
+                copy_1k_to_lds<(piece % CPW) * 1024>(wsbuf, jl * TILE_BYTES + KT_BYTES + wave * (CPW * 1024),
                                                      smem + 2 * KT_BYTES + (jl & 1) * KT_BYTES + wave * (CPW * 1024), lane);
         }
     };
@@ -450,7 +455,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // The code generator otherwise sinks a hook's arithmetic into the later block that uses its result, away from the
     // MFMA it was meant to run behind; an empty volatile asm that takes and returns the values keeps it in place.
 #define PASA_PIN2(a, b) asm volatile("" : "+v"(a), "+v"(b))
-    constexpr int PF = 4;
+#ifndef PASA_PF
+#define PASA_PF 3
+#endif
+    constexpr int PF = PASA_PF;
     constexpr int NM1 = 4 * KS;      // MFMAs of the first GEMM:  n = kb * KS + ks
     constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM: n = cb * 8 + kk
     auto gemm1 = [&](int jt, auto&& hook) {   // S'^T of tile jt: 128 keys x 32 queries
