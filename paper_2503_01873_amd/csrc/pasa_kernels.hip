@@ -666,6 +666,35 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 m = mnew;
                 mref = mnew;
             }
+            // ---- fp32 variants: global recovering (step 3) and the output rescale factor now, before the exponentials.
+            // Only the running sum needs l'; the rest is a chain of some forty dependent scalar operations whose
+            // latency is hidden when the exponentials that follow can issue in between. ----
+            float g = 1.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
+            bool drop = false;    // this row's tile j is too far below the running maximum to matter
+            float l_ep = 0.f, l_ec = 1.f;   // l <- l_ep * l + l_ec * l'  (first tile: l = l')
+            if (!STRICT && !NAIVE) {
+                // Written without branches (the first tile and rows that see nothing of the tile select their values at
+                // the end) so that it stays in one block with the exponentials.
+                // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division by
+                // j is a multiplication by 1/j here
+                const float jm1 = (float)j, rj = 1.0f / (float)(j + 1);
+                const float Fn = (jm1 * F + sbar) * rj;
+                const float dpp = inva * (F - Fn);
+                const float dpc = inva * (sbar - Fn);
+                const float mn = __builtin_fmaxf(m + dpp, mx + dpc);
+                const float dp = (m - mn) + dpp;
+                const float dc = (mx - mn) + dpc;
+                const bool keep = first || unseen;        // no recovering step for this row
+                drop = !keep && dc < -60.f;
+                // dropped: O_j = e^{dp} O_{j-1}, same stored output at a smaller scale; else the stored output is rescaled
+                const float g_all = exp_nat((dp + Lc) - dc);
+                g = (keep || drop) ? 1.f : g_all;
+                Lc = first ? 0.f : unseen ? Lc : drop ? dp + Lc : dc;
+                l_ep = first ? 0.f : unseen ? 1.f : exp_nat(dp);
+                l_ec = unseen ? 0.f : first ? 1.f : exp_nat(dc);
+                F = first ? sbar : unseen ? F : Fn;
+                m = first ? mx : unseen ? m : mn;
+            }
             // ---- P = exp(S' - m') rounded to fp16; l' = sum of the rounded P ----
             float lsum;
             {
@@ -700,46 +729,21 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 if (STRICT) lsum = (float)(_Float16)lsum;
             }
 
-            // ---- global recovering (step 3), the running sum (step 4) and the output rescale factor ----
-            float g = 1.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
-            bool drop = false;    // this row's tile j is too far below the running maximum to matter
+            // ---- the running sum (step 4); STRICT16: the whole of step 3 and 4 in fp16 ----
             if (NAIVE) {
                 l = e_old * l + lsum;
                 g = e_old;
+            } else if (!STRICT) {
+                l = first ? lsum : l_ep * l + l_ec * lsum;
             } else if (first) {
                 F = sbar;
                 m = mx;
                 l = lsum;
-                Lc = 0.f;
                 ec_s = 1.f;
                 ep_s = 0.f;
-            } else if (unseen) {
-                if (STRICT) {     // O <- fp16(0 * 0) + fp16(1 * O)
-                    ec_s = 0.f;
-                    ep_s = 1.f;
-                }
-            } else if (!STRICT) {
-                // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division
-                // by j is a multiplication by 1/j here
-                const float jm1 = (float)j, rj = 1.0f / (float)(j + 1);
-                const float Fn = (jm1 * F + sbar) * rj;
-                const float dpp = inva * (F - Fn);
-                const float dpc = inva * (sbar - Fn);
-                const float mn = __builtin_fmaxf(m + dpp, mx + dpc);
-                const float dp = (m - mn) + dpp;
-                const float dc = (mx - mn) + dpc;
-                const float ep = exp_nat(dp), ec = exp_nat(dc);
-                l = ep * l + ec * lsum;
-                F = Fn;
-                m = mn;
-                drop = dc < -60.f;
-                if (drop) {
-                    Lc = dp + Lc;             // O_j = e^{dp} O_{j-1}: same stored output, smaller scale
-                    g = 1.f;
-                } else {
-                    g = exp_nat((dp + Lc) - dc);
-                    Lc = dc;
-                }
+            } else if (unseen) {      // O <- fp16(0 * 0) + fp16(1 * O)
+                ec_s = 0.f;
+                ep_s = 1.f;
             } else {
                 // every operation rounded to fp16, in the order Algorithm 1 states them
                 const _Float16 jm1 = (_Float16)(float)j, jn = (_Float16)(float)(j + 1);
