@@ -7,8 +7,8 @@
 //                 is rounded once to fp16, and both K' and V are re-tiled so that the main kernel's LDS image of
 //                 a tile is a straight copy whose MFMA fragments are single conflict-free 128-bit LDS reads.
 //
-//  pasa_fwd       Algorithm 1's main loops.  One workgroup = 4 wavefronts = 256 query rows; each wavefront owns
-//                 64 query rows and sweeps the key tiles.  Both GEMMs are computed transposed on
+//  pasa_fwd       Algorithm 1's main loops.  One workgroup = 8 wavefronts = 256 query rows; each wavefront owns
+//                 32 query rows and sweeps the key tiles.  Both GEMMs are computed transposed on
 //                 v_mfma_f32_32x32x16_f16:
 //                     S'^T = K' Q^T      (A = K' fragment from LDS, B = Q fragment held in registers)
 //                     O^T += V^T P^T     (A = V^T fragment from LDS, B = P^T taken straight from the S'^T accumulators)
@@ -99,8 +99,11 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     constexpr int CH = D / 8;            // 16-byte chunks per key
     constexpr int KL = 256 / CH;         // key lanes
     constexpr int KPT = T / KL;          // keys per thread
-    __shared__ double psum[KL][D];
-    __shared__ _Float16 vs[T][D + 8];    // +8 halfs: rows start 16 bytes apart in bank space
+    // the two halves of the work (see blockIdx.y below) use the same LDS bytes
+    constexpr size_t PSUM_BYTES = sizeof(double) * KL * D, VS_BYTES = sizeof(_Float16) * T * (D + 8);
+    __shared__ __attribute__((aligned(16))) char lds_raw[PSUM_BYTES > VS_BYTES ? PSUM_BYTES : VS_BYTES];
+    double (*psum)[D] = reinterpret_cast<double (*)[D]>(lds_raw);
+    _Float16 (*vs)[D + 8] = reinterpret_cast<_Float16 (*)[D + 8]>(lds_raw);   // +8 halfs: rows start 16 bytes apart in bank space
 
     const size_t tile = blockIdx.x;                      // (batch, KV head, key tile)
     const size_t head = tile / ntile;
@@ -110,6 +113,30 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     const _Float16* ksrc = k + src_off;
     const int tid = threadIdx.x;
     const int c8 = tid % CH, kl = tid / CH;
+
+    // blockIdx.y picks the half of the work: 0 shifts the keys, 1 re-tiles the values (twice the blocks in flight
+    // for a pass that is bound by memory latency, not by arithmetic)
+    if (blockIdx.y == 1) {
+        const _Float16* vsrc = v + src_off;
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int n = kl + KL * i;
+            *reinterpret_cast<h8*>(&vs[n][8 * c8]) =
+                n < nvalid ? load_h8(vsrc + n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
+        }
+        __syncthreads();
+        _Float16* vdst = wsout + tile * (size_t)(2 * T * D) + T * D;
+        for (int chunk = tid; chunk < 16 * D; chunk += 256) {
+            const int c = chunk % D;
+            const int kh = chunk / D;            // (n/16)*2 + h
+            const int nb = (kh >> 1) * 16 + (kh & 1) * 4;
+            h8 out;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out[e] = vs[nb + (e >> 2) * 8 + (e & 3)][c];
+            *reinterpret_cast<h8*>(vdst + (size_t)chunk * 8) = out;
+        }
+        return;
+    }
 
     h8 kv[KPT];
     double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -122,16 +149,6 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) psum[kl][8 * c8 + e] = s[e];
-
-    if (v != nullptr) {
-        const _Float16* vsrc = v + src_off;
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const int n = kl + KL * i;
-            *reinterpret_cast<h8*>(&vs[n][8 * c8]) =
-                n < nvalid ? load_h8(vsrc + n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
-        }
-    }
     __syncthreads();
 
     double mean[8];
@@ -167,19 +184,6 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
             if (n < nvalid) *reinterpret_cast<h8*>(plain_out + src_off + n * D + 8 * c8) = out;
         } else {
             *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)c8 * T + n) * 8) = out;
-        }
-    }
-
-    if (v != nullptr) {
-        _Float16* vdst = wsout + tile * (size_t)(2 * T * D) + T * D;
-        for (int chunk = tid; chunk < 16 * D; chunk += 256) {
-            const int c = chunk % D;
-            const int kh = chunk / D;            // (n/16)*2 + h
-            const int nb = (kh >> 1) * 16 + (kh & 1) * 4;
-            h8 out;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) out[e] = vs[nb + (e >> 2) * 8 + (e & 3)][c];
-            *reinterpret_cast<h8*>(vdst + (size_t)chunk * 8) = out;
         }
     }
 }
@@ -862,7 +866,7 @@ hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_
                             hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
-    const dim3 grid((unsigned)((size_t)B * Hkv * ntile));
+    const dim3 grid((unsigned)((size_t)B * Hkv * ntile), v != nullptr ? 2u : 1u);   // y: keys / values
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
                            (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode, in_bf16);
