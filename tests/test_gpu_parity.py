@@ -434,6 +434,44 @@ def test_decoding_against_a_cache(Nq):
     assert compare(o2, o3)["maxabs"] <= 2e-3
 
 
+# ------------------------------------------------------------------ capture into a HIP graph
+
+def test_graph_capture_and_replay():
+    """pasa_attn_fwd_ex with a caller workspace allocates nothing and only enqueues kernels, so it can be
+    captured into a HIP graph; every replay must give the eager result for the inputs then in the buffers."""
+    import torch
+    dev = torch.device("cuda:0")
+    w = _small(3, 1000, Hq=4, Hkv=2)
+    scale = f32(w.scale)
+    inputs = []
+    for seed in (w.seed, w.seed + 1, w.seed + 2):
+        inputs.append(gen_full(Workload(**{**w.__dict__, "seed": seed})))
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in inputs[0])
+    to = torch.zeros_like(tq)
+    wsb = P.pasa_attn_fwd_workspace(w.B, w.Hq, w.Hkv, w.N, w.d)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    args = (w.B, w.Hq, w.Hkv, w.N, w.d, True, scale)
+    eager = []
+    for q, k, v in inputs:                       # eager results first (also warms the kernels up before capture)
+        tq.copy_(torch.from_numpy(q)); tk.copy_(torch.from_numpy(k)); tv.copy_(torch.from_numpy(v))
+        P.pasa_attn_fwd_ex(tq, tk, tv, to, *args, ws, wsb, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        eager.append(to.cpu().numpy().copy())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        P.pasa_attn_fwd_ex(tq, tk, tv, to, *args, ws, wsb, torch.cuda.current_stream())
+    for rep in range(2):
+        for i, (q, k, v) in enumerate(inputs):
+            tq.copy_(torch.from_numpy(q)); tk.copy_(torch.from_numpy(k)); tv.copy_(torch.from_numpy(v))
+            to.fill_(float("nan"))
+            ws.zero_()                           # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            got = to.cpu().numpy()
+            assert np.array_equal(got.view(np.uint16), eager[i].view(np.uint16)), (rep, i)
+
+
 # ------------------------------------------------------------------ full sizes, sampled, in the benchmark's launch configuration
 
 def _sampled_check(w, variant, units, tol_p999=2e-3):
