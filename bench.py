@@ -85,7 +85,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--variant", default="mixed", choices=["mixed", "strict16", "s16", "naive16"])
+    ap.add_argument("--variant", default="mixed", choices=["mixed", "strict16", "s16", "naive16", "direct"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -102,7 +102,8 @@ def main():
     import paper_2503_01873_amd as P
     from workloads import workload, gen_q_head, gen_kv_head
 
-    variant = {"mixed": P.MIXED, "strict16": P.STRICT16, "s16": P.S16, "naive16": P.NAIVE16}[args.variant]
+    variant = {"mixed": P.MIXED, "strict16": P.STRICT16, "s16": P.S16, "naive16": P.NAIVE16,
+               "direct": P.DIRECT}[args.variant]
     w = workload(WORKLOAD)
     scale = float(np.float32(w.scale))
     dev = torch.device("cuda:0")
@@ -183,7 +184,11 @@ def main():
             got = o_host[0, h, r0:r0 + 128].astype(np.float64)
             num += ((got - gold) ** 2).sum()
             den += (gold ** 2).sum()
-            if pol is not None:
+            if variant == P.DIRECT:      # the recovery that is not the paper's: its own oracle function
+                ref = po.direct_rows(q_heads[h][r0:r0 + 128], kk[:r0 + 128], vv[:r0 + 128], scale, True,
+                                     po.default_beta(), 128, po.MIXED, r0).astype(np.float64)
+                maxabs = max(maxabs, float(np.abs(got - ref).max()))
+            elif pol is not None:
                 ref = po.pasa_rows(q_heads[h][r0:r0 + 128], kk[:r0 + 128], vv[:r0 + 128], scale, True,
                                    po.default_beta(), 128, pol, r0).astype(np.float64)
                 maxabs = max(maxabs, float(np.abs(got - ref).max()))

@@ -48,7 +48,14 @@ typedef enum {
     PASA_STRICT16 = 1, /* Algorithm 1 as printed: S', P, Sbar', F, all Delta terms, m, l, P V and O rounded to fp16 */
     PASA_NAIVE16 = 2,  /* no shift (beta forced to 0): raw S = Q K^T rounded to fp16, then scaled; rest fp32.
                           This is the partially low-precision FlashAttention that overflows (section 2.1, Table 4). */
-    PASA_S16 = 3       /* shifted like MIXED, S' rounded to fp16 as it leaves the matrix core, statistics and O fp32 */
+    PASA_S16 = 3,      /* shifted like MIXED, S' rounded to fp16 as it leaves the matrix core, statistics and O fp32 */
+    PASA_DIRECT = 4    /* NOT the paper's recovering step ("direct-bias recovery").  Same idea of a shifted K' so that the
+                          scores stay small, precision allocation of MIXED, but the shift vector of a tile is the fp16
+                          vector k0 = fp16(beta * mean_tile(K)), K' = fp16((K - k0) * scale), and the removed bias is
+                          added back as scale * (q . k0) (legal by Eq. (9): any shift leaves softmax unchanged)
+                          followed by ordinary online softmax (Eq. (4)-(8)).  There is no pseudo-average Sbar' and no
+                          factor beta/(1-beta), so the rounding noise of K' is not amplified; costs eight more MFMAs per
+                          tile.  PASA_SHIFT_MATRIX does not apply to it. */
 } pasa_variant;
 
 /* How the key pre-processing loop of Algorithm 1 forms K' (Eq. (10), (11)). */
@@ -86,8 +93,9 @@ typedef struct {
 int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
                   int B, int Hq, int Hkv, int N, int d, int causal, float scale, void* stream);
 
-/* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes (shifted keys K' and re-tiled values,
- * both fp16: 4*B*Hkv*ceil(N/128)*128*d bytes).  Returns 0 if the sizes are invalid. */
+/* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes: shifted keys K' and re-tiled values, both fp16
+ * (4*B*Hkv*ceil(N/128)*128*d bytes), then one fp16 shift vector per key tile (2*B*Hkv*ceil(N/128)*d bytes, rounded up
+ * to a multiple of 256; written and read by PASA_DIRECT only).  Returns 0 if the sizes are invalid. */
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
@@ -130,6 +138,11 @@ int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d,
 /* The same with PASA_SHIFT_MATRIX: K'^T = fp16(K^T M16), M16 the entrywise fp16 rounding of Eq. (10)'s M with
  * alpha = 1/kscale.  N must be a multiple of 128. */
 int pasa_shift_keys_matrix(const void* k, void* kprime, int B, int Hkv, int N, int d,
+                           double beta, double kscale, void* stream);
+
+/* The shift of PASA_DIRECT: k0[b, h, t, :] = fp16(beta * mean of key tile t) ([B, Hkv, ceil(N/128), d], DEVICE, written)
+ * and K' = fp16((K - k0) * kscale) in the plain layout. */
+int pasa_shift_keys_direct(const void* k, void* kprime, void* k0, int B, int Hkv, int N, int d,
                            double beta, double kscale, void* stream);
 
 /* Host-only, fp64: solves the optimal accuracy condition beta/(1-beta) = f(beta) (Eq. (16), (20)-(22)) by

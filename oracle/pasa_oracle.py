@@ -15,6 +15,9 @@ Contents (citations are to the paper's sections / equations / Algorithm 1):
   pasa_rows              Algorithm 1 step by step with a per-quantity precision policy
   fa_rows                plain blocked FlashAttention, Eq. (1)-(8), with the precision allocations of
                          section 1.2 (used for the beta = 0 special case and the overflow baseline)
+  direct_rows            NOT the paper's recovering step: the same key shift, but the removed bias is added back
+                         as the dot product of the query with the shift vector (Eq. (9) allows any shift), which
+                         avoids multiplying the rounding noise of Sbar' by beta/(1-beta).  Kept under its own name.
   rmse                   relative RMSE, Eq. (19)
 
 Pins (tests/test_oracle_*.py): Table 3 and the three printed beta values; Theorem 2.1; Eq. (13), (14);
@@ -269,6 +272,90 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
             out = (O / l[:, None]).astype(np.float16)
     if info is not None:
         info.update(smax=smax, s_nonfinite=s_nonfinite, s_seen=s_seen)
+    return out
+
+
+# ----------------------------------------------------------------------------------------------
+# Direct-bias recovery (not in the paper; same shift, different recovering step)
+# ----------------------------------------------------------------------------------------------
+
+def direct_shift_keys(K: np.ndarray, beta: float, scale: float, T: int = 128):
+    """Per key tile: k0 = fl16(beta * mean_tile(K)) and K' = fl16((K - k0) * scale).  Returns (K' [N,d] fp16,
+    k0 [ntile,d] fp16).  The shift vector is itself an fp16 vector, so S = S' + scale * Q k0 holds exactly for the
+    K' before its own rounding (softmax translation invariance, Eq. (9), with K0 = k0)."""
+    N, d = K.shape
+    K64 = np.asarray(K).astype(np.float64)
+    ntile = -(-N // T)
+    Kp = np.empty((N, d))
+    k0 = np.empty((ntile, d))
+    for jt in range(ntile):
+        tile = K64[jt * T:(jt + 1) * T]
+        kbar = tile.sum(axis=0) / tile.shape[0]                     # exact sum, one division
+        k0[jt] = fl(beta * kbar, "f16")
+        Kp[jt * T:(jt + 1) * T] = (tile - k0[jt][None, :]) * scale    # the difference is exact in fp64
+    with np.errstate(over="ignore"):
+        return Kp.astype(np.float16), k0.astype(np.float16)
+
+
+def direct_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128, policy: Policy = MIXED,
+                row0: int = 0, info: dict | None = None):
+    """Blocked attention with the key shift of Eq. (10), (11) and the bias added back directly.
+
+    Per tile j and query row: S' = Q K'_j^T as in Algorithm 1 (so the scores stay small), c_j = scale * (Q . k0_j),
+    local maximum m'_j, P = exp(S' - m'_j), and then ordinary online softmax (Eq. (4)-(8)) on the level m'_j + c_j.
+    """
+    st, pS, pP, pO = policy.stat, policy.S, policy.P, policy.O
+    Q64 = np.asarray(Q).astype(np.float64)
+    V64 = np.asarray(V).astype(np.float64)
+    N, d = K.shape
+    R = Q64.shape[0]
+    Kp, k0 = direct_shift_keys(np.asarray(K), beta, scale, T)
+    Kp64, k064 = Kp.astype(np.float64), k0.astype(np.float64)
+    rows = row0 + np.arange(R)
+    ntile = np.minimum(rows // T + 1, -(-N // T)) if causal else np.full(R, -(-N // T))
+    Mx = np.zeros(R)
+    l = np.zeros(R)
+    O = np.zeros((R, d))
+    smax = 0.0
+    with np.errstate(over="ignore", invalid="ignore", divide="ignore"):
+        for jt in range(int(ntile.max())):
+            a = np.nonzero(ntile > jt)[0]
+            Kt = Kp64[jt * T:(jt + 1) * T]
+            Vt = V64[jt * T:(jt + 1) * T]
+            S = fl(Q64[a] @ Kt.T, pS)
+            smax = max(smax, float(np.abs(S[np.isfinite(S)]).max()))
+            c = fl(scale * fl(Q64[a] @ k064[jt], "f32"), st)           # the removed bias of this tile, per row
+            if causal:
+                keys = jt * T + np.arange(Kt.shape[0])
+                S = np.where(keys[None, :] > rows[a][:, None], -np.inf, S)
+            mloc = S.max(axis=1)
+            P = fl(np.exp(fl(S - mloc[:, None], pS)), pP)
+            lloc = fl(P.sum(axis=1), st)
+            Ot = fl(P @ Vt, pO)
+            L = fl(mloc + c, st)                                        # level of this tile's maximum
+            if jt == 0:
+                Mx[a], l[a], O[a] = L, lloc, Ot
+                continue
+            Mn = np.maximum(Mx[a], L)
+            ep = fl(np.exp(fl(Mx[a] - Mn, st)), st)
+            ec = fl(np.exp(fl(L - Mn, st)), st)
+            l[a] = fl(fl(ep * l[a], st) + fl(ec * lloc, st), st)
+            O[a] = fl(fl(ec[:, None] * Ot, pO) + fl(ep[:, None] * O[a], pO), pO)
+            Mx[a] = Mn
+        out = (O / l[:, None]).astype(np.float16)
+    if info is not None:
+        info.update(smax=smax)
+    return out
+
+
+def direct_bhnd(q, k, v, scale, causal, beta, T=128, policy=MIXED) -> np.ndarray:
+    B, Hq, N, d = q.shape
+    Hkv = k.shape[1]
+    out = np.empty((B, Hq, N, d), np.float16)
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // (Hq // Hkv)
+            out[b, h] = direct_rows(q[b, h], k[b, hk], v[b, hk], scale, causal, beta, T, policy)
     return out
 
 

@@ -9,7 +9,7 @@ from __future__ import annotations
 import ctypes
 import os
 
-MIXED, STRICT16, NAIVE16, S16 = 0, 1, 2, 3
+MIXED, STRICT16, NAIVE16, S16, DIRECT = 0, 1, 2, 3, 4
 SHIFT_MEAN, SHIFT_MATRIX = 0, 1
 IO_F16, IO_BF16 = 0, 1
 
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
     L.pasa_shift_keys.restype = ci
     L.pasa_shift_keys_matrix.argtypes = [vp, vp, ci, ci, ci, ci, cd, cd, vp]
     L.pasa_shift_keys_matrix.restype = ci
+    L.pasa_shift_keys_direct.argtypes = [vp, vp, vp, ci, ci, ci, ci, cd, cd, vp]
+    L.pasa_shift_keys_direct.restype = ci
     L.pasa_optimal_beta.argtypes = [cd, ci, ci]
     L.pasa_optimal_beta.restype = cd
     L.pasa_invariance_rounded.argtypes = [cd, ci, ci]
@@ -175,3 +177,9 @@ def pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, workspa
     st = lib().pasa_attn_fwd_chunk(_ptr(q), _ptr(o), B, Hq, Hkv, Nq, row0, N, d, int(causal), float(scale),
                                    ctypes.byref(opts), _ptr(workspace), int(workspace_bytes), _stream(stream))
     return _check(st, "pasa_attn_fwd_chunk", check)
+
+
+def pasa_shift_keys_direct(k, kprime, k0, B, Hkv, N, d, beta, kscale, stream=None, check=True) -> int:
+    st = lib().pasa_shift_keys_direct(_ptr(k), _ptr(kprime), _ptr(k0), B, Hkv, N, d, float(beta), float(kscale),
+                                      _stream(stream))
+    return _check(st, "pasa_shift_keys_direct", check)

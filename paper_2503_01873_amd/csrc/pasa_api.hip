@@ -87,11 +87,32 @@ double pasa_optimal_beta(double beta0, int n, int tp)
     return beta;
 }
 
+}  // extern "C"
+
+namespace {
+
+// Workspace layout: the K'/V tiles, then (used by PASA_DIRECT only) one fp16 shift vector of d halfs per tile.
+size_t tiles_bytes(int B, int Hkv, int N, int d)
+{
+    const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
+    return (size_t)4 * (size_t)B * (size_t)Hkv * ntile * kShiftTile * (size_t)d;
+}
+
+size_t k0_bytes(int B, int Hkv, int N, int d)
+{
+    const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;
+    const size_t raw = (size_t)2 * (size_t)B * (size_t)Hkv * ntile * (size_t)d;
+    return (raw + 255) / 256 * 256;
+}
+
+}  // namespace
+
+extern "C" {
+
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
 {
     if (check_shape(B, Hq, Hkv, N, d) != PASA_OK) return 0;
-    const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
-    return (size_t)4 * (size_t)B * (size_t)Hkv * ntile * kShiftTile * (size_t)d;
+    return tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d);
 }
 
 }  // extern "C"
@@ -111,18 +132,20 @@ void rounded_shift_matrix(double beta, double kscale, double* a_minus_b, double*
 }
 
 int shift_keys_common(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale,
-                      int matrix_mode, void* stream)
+                      int shift_mode, void* k0out, void* stream)
 {
     const int st = check_shape(B, Hkv, Hkv, N, d);
     if (st != PASA_OK) return st;
     if (k == nullptr || kprime == nullptr || !aligned(k, 16) || !aligned(kprime, 16) || k == kprime) return PASA_EINVAL;
     if (!(beta >= 0.0) || !(beta < 1.0) || !isfinite(kscale) || !(kscale > 0.0)) return PASA_EINVAL;
     double c1 = beta, c2 = kscale;
-    if (matrix_mode) {
+    if (shift_mode == PASA_PREP_MATRIX) {
         if (N % kShiftTile != 0) return PASA_EUNSUPPORTED;   // M is a full 128 x 128 matrix
         rounded_shift_matrix(beta, kscale, &c1, &c2);
     }
-    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, matrix_mode, 0,
+    if (shift_mode == PASA_PREP_DIRECT && (k0out == nullptr || !aligned(k0out, 16) || k0out == kprime || k0out == k))
+        return PASA_EINVAL;
+    const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, shift_mode, 0, k0out,
                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
@@ -133,13 +156,19 @@ extern "C" {
 
 int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale, void* stream)
 {
-    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, 0, stream);
+    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, PASA_PREP_MEAN, nullptr, stream);
 }
 
 int pasa_shift_keys_matrix(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale,
                            void* stream)
 {
-    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, 1, stream);
+    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, PASA_PREP_MATRIX, nullptr, stream);
+}
+
+int pasa_shift_keys_direct(const void* k, void* kprime, void* k0, int B, int Hkv, int N, int d, double beta, double kscale,
+                           void* stream)
+{
+    return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, PASA_PREP_DIRECT, k0, stream);
 }
 
 namespace {
@@ -161,7 +190,8 @@ int resolve(const pasa_opts* opts, float scale, Params* out)
     if (!isfinite(scale) || !(scale > 0.f)) return PASA_EINVAL;
     pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr, PASA_SHIFT_MEAN, PASA_IO_F16};
     if (opts != nullptr) op = *opts;
-    if (op.variant < PASA_MIXED || op.variant > PASA_S16) return PASA_EINVAL;
+    if (op.variant < PASA_MIXED || op.variant > PASA_DIRECT) return PASA_EINVAL;
+    if (op.variant == PASA_DIRECT && op.shift_mode == PASA_SHIFT_MATRIX) return PASA_EINVAL;   // it has its own shift
     if (op.shift_mode != PASA_SHIFT_MEAN && op.shift_mode != PASA_SHIFT_MATRIX) return PASA_EINVAL;
     if (op.io_dtype != PASA_IO_F16 && op.io_dtype != PASA_IO_BF16) return PASA_EINVAL;
     if (op.shift_tile != 0 && op.shift_tile != kShiftTile) return PASA_EUNSUPPORTED;
@@ -208,8 +238,10 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
     const size_t need = pasa_attn_fwd_workspace(B, Hkv, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
-    const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, pr.matrix_mode,
-                                          pr.io_bf16, static_cast<hipStream_t>(stream));
+    const int mode = pr.variant == PASA_DIRECT ? PASA_PREP_DIRECT : pr.matrix_mode ? PASA_PREP_MATRIX : PASA_PREP_MEAN;
+    void* k0out = static_cast<char*>(workspace) + tiles_bytes(B, Hkv, N, d);
+    const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, mode, pr.io_bf16,
+                                          k0out, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
 
@@ -237,6 +269,7 @@ int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, 
     if (st != PASA_OK) return st;
     PasaLaunch p;
     p.q = q; p.ws = workspace; p.o = o;
+    p.k0 = static_cast<const char*>(workspace) + tiles_bytes(B, Hkv, N, d);
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.d = d;
     p.Nq = Nq; p.row0 = causal ? row0 : 0;
     p.causal = causal;

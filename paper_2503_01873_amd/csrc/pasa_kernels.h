@@ -5,12 +5,15 @@
 #include <hip/hip_runtime.h>
 
 // kernel precision variants; values equal the public pasa_variant enumerators
-enum { PASA_K_MIXED = 0, PASA_K_STRICT16 = 1, PASA_K_NAIVE16 = 2, PASA_K_S16 = 3 };
+enum { PASA_K_MIXED = 0, PASA_K_STRICT16 = 1, PASA_K_NAIVE16 = 2, PASA_K_S16 = 3, PASA_K_DIRECT = 4 };
+// how the pre-processing kernel forms K'
+enum { PASA_PREP_MEAN = 0, PASA_PREP_MATRIX = 1, PASA_PREP_DIRECT = 2 };
 
 struct PasaLaunch {
     const void* q;
     const void* ws;   // per (batch, KV head, key tile): shifted-key tile then value tile, fragment-major layout
     void* o;
+    const void* k0;   // PASA_K_DIRECT: per (batch, KV head, key tile) the fp16 shift vector, d halfs each
     int B, Hq, Hkv, N, d;   // N: keys
     int Nq, row0;           // query rows given, and the sequence position of the first of them
     int causal;
@@ -26,12 +29,13 @@ struct PasaLaunch {
 // Shift + re-tile K (and re-tile V when v != nullptr).  plain_out != nullptr: K' goes there in the
 // plain [B,Hkv,N,d] layout and ws is not written.
 // in_bf16: k and v hold bf16 and are converted to fp16 as they are loaded (outputs stay fp16).
-// matrix_mode == 0: K' = fp16((K - beta * tile mean) * kscale).
-// matrix_mode == 1: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
+// PASA_PREP_MEAN:   K' = fp16((K - beta * tile mean) * kscale).
+// PASA_PREP_MATRIX: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
 //                   matrix a I + b (J - I) when beta carries a - b and kscale carries b (N % 128 == 0 only).
+// PASA_PREP_DIRECT: k0 = fp16(beta * tile mean) goes to k0out ([B, Hkv, tiles, d]) and K' = fp16((K - k0) * kscale).
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
-                            int B, int Hkv, int N, int d, double beta, double kscale, int matrix_mode, int in_bf16,
-                            hipStream_t stream);
+                            int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
+                            void* k0out, hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);
 

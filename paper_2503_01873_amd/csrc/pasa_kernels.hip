@@ -93,8 +93,9 @@ __device__ inline _Float16 double_to_half_rn(double x)
 template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
                                                     _Float16* __restrict__ wsout,
-                                                    _Float16* __restrict__ plain_out, int N, int ntile,
-                                                    double beta, double kscale, int matrix_mode, int in_bf16)
+                                                    _Float16* __restrict__ plain_out, _Float16* __restrict__ k0out,
+                                                    int N, int ntile, double beta, double kscale, int shift_mode,
+                                                    int in_bf16)
 {
     constexpr int CH = D / 8;            // 16-byte chunks per key
     constexpr int KL = 256 / CH;         // key lanes
@@ -158,7 +159,15 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
 #pragma unroll 4
         for (int r = 0; r < KL; ++r) tot += psum[r][8 * c8 + e];
         // the tile's own key count, so that Eq. (14) holds for a ragged tile too; the matrix form needs the plain sum
-        mean[e] = matrix_mode ? tot : tot / (double)nvalid;
+        mean[e] = shift_mode == PASA_PREP_MATRIX ? tot : tot / (double)nvalid;
+        // direct-bias recovery: the shift vector k0 = fp16(beta * mean) is itself an fp16 vector
+        if (shift_mode == PASA_PREP_DIRECT) mean[e] = (double)double_to_half_rn(__dmul_rn(beta, mean[e]));
+    }
+    if (shift_mode == PASA_PREP_DIRECT && kl == 0) {
+        h8 k0v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) k0v[e] = (_Float16)mean[e];      // exact: already an fp16 value
+        *reinterpret_cast<h8*>(k0out + tile * (size_t)D + 8 * c8) = k0v;
     }
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
@@ -167,7 +176,9 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             double r;
-            if (matrix_mode) {
+            if (shift_mode == PASA_PREP_DIRECT) {
+                r = __dmul_rn(__dsub_rn((double)kv[i][e], mean[e]), kscale);     // (K - k0) is exact in fp64
+            } else if (shift_mode == PASA_PREP_MATRIX) {
                 // K'^T = K^T M with M = a I + b (J - I) entrywise rounded to fp16 (Eq. (10), (11) as a GEMM):
                 // sum_p M[p,q] K[p,c] = (a - b) K[q,c] + b sum_p K[p,c].  Here beta carries (a - b) and kscale
                 // carries b; both products are exact in fp64 and the sum rounds once.
@@ -267,14 +278,16 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
-              int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale, int io_bf16,
+              const _Float16* __restrict__ k0, int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale,
+              int io_bf16,
               unsigned long long* ovf_s, unsigned long long* nonfinite_o)
 {
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
     constexpr int CB = D / 32;   // 32-channel row blocks of O^T
-    constexpr bool S16 = (VAR != PASA_K_MIXED);                 // S' rounded to fp16 as it leaves the matrix core
+    constexpr bool S16 = (VAR != PASA_K_MIXED && VAR != PASA_K_DIRECT);   // S' rounded to fp16 as it leaves the matrix core
     constexpr bool STRICT = (VAR == PASA_K_STRICT16);
     constexpr bool NAIVE = (VAR == PASA_K_NAIVE16);
+    constexpr bool DIRECT = (VAR == PASA_K_DIRECT);               // bias added back as scale * (q . k0), no pseudo-average
     constexpr int KT_BYTES = T * D * 2;                         // one K' (or V) tile
     constexpr int TILE_BYTES = 2 * KT_BYTES;                    // workspace stride: K' tile then V tile
     constexpr int CPW = KT_BYTES / 1024 / 8;                    // 1 KiB copies per wave per K' (or V) tile
@@ -344,7 +357,18 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     const __amdgpu_buffer_rsrc_t wsbuf =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wsbase), 0, ntile * TILE_BYTES, 0x00020000);
 
+    // DIRECT: the shift vectors k0 of this head's tiles (D halfs each); a tile's vector goes to one of two 256-byte LDS
+    // slots behind the tile buffers with one wave-wide 4-byte-per-lane copy (for D = 64 its upper half is padding)
+    const __amdgpu_buffer_rsrc_t k0buf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<_Float16*>(DIRECT ? k0 + ((size_t)(b * Hkv + hk) * ntile) * D : q), 0, DIRECT ? ntile * D * 2 : 0,
+        0x00020000);
+    auto issue_k0 = [&](int j) {
+        if (DIRECT && wave == 0)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(k0buf, (__attribute__((address_space(3))) void*)(smem + 4 * KT_BYTES + (j & 1) * 256),
+                                                     4, lane * 4, j * D * 2, 0, 0);
+    };
     auto issue_k = [&](int j) {
+        issue_k0(j);
         const int src = j * TILE_BYTES;
         char* dst = smem + (j & 1) * KT_BYTES;
 #pragma unroll
@@ -404,6 +428,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         constexpr int piece = decltype(piece_c)::value;       // 0 .. 2*CPW-1: K' pieces first, then V pieces
         const int jl = sg >> 1;
         if (piece < CPW) {
+            if (piece == 0 && jl + 1 < J_wg) issue_k0(jl + 1);
             if (jl + 1 < J_wg)
                 copy_1k_to_lds<(piece % CPW) * 1024>(wsbuf, (jl + 1) * TILE_BYTES + wave * (CPW * 1024),
                                                      smem + ((jl + 1) & 1) * KT_BYTES + wave * (CPW * 1024), lane);
@@ -451,7 +476,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     for (int kb = 0; kb < 4; ++kb) ps[kb] = pm[kb] = 0.f;
     // MIXED takes the two row reductions of S'(j) while the second GEMM of tile j-1 runs (same wave, co-issued with
     // its MFMAs) and applies the output rescale under the first GEMM, which shortens the vector part.
-    constexpr bool EARLY = (VAR == PASA_K_MIXED) && !INSTR;
+    constexpr bool EARLY = (VAR == PASA_K_MIXED || DIRECT) && !INSTR;
+    float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile whose S' was computed last
 
     // Both GEMMs run as one chain of MFMAs per accumulator block (the block index is the slow one), with the LDS
     // fragments PF instructions ahead.  hook(n) is vector work of the same wave placed behind MFMA n; it is issued
@@ -471,10 +497,22 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         h8 a[PF];
 #pragma unroll
         for (int n = 0; n < PF; ++n) a[n] = frag(n);
+        if (DIRECT) {
+            // q . k0 on the matrix core: k0 is row 0 of an otherwise zero 32-row A operand, accumulated in the block
+            // of S' that is written last; row 0 of the result sits in element 0 of lanes 0-31
+            const _Float16* lds_k0 = reinterpret_cast<const _Float16*>(smem + 4 * KT_BYTES + (jt & 1) * 256);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                h8 ak = (h8)(_Float16)0;
+                if (lq == 0) ak = *reinterpret_cast<const h8*>(lds_k0 + (2 * ks + lh) * 8);
+                S[3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak, Qf[ks], ks ? S[3] : (f16v)0.f, 0, 0, 0);
+            }
+        }
         PASA_FENCE();
 #pragma unroll
         for (int n = 0; n < NM1; ++n) {
             const int kb = n / KS, ks = n % KS;
+            if (DIRECT && n == KS) cj = scale * sum32(S[3][0]);     // before the last block's chain reuses S[3]
             if (ks == 0)
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], (f16v)0.f, 0, 0, 0);
             else
@@ -575,7 +613,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     float sacc = ks ? ps[kb] : 0.f, macc = ks ? pm[kb] : -__builtin_inff();
 #pragma unroll
                     for (int i = ks * PER; i < (ks + 1) * PER; ++i) {
-                        sacc += S[kb][i];
+                        if (!DIRECT) sacc += S[kb][i];
                         macc = __builtin_fmaxf(macc, S[kb][i]);
                     }
                     PASA_PIN2(sacc, macc);
@@ -585,7 +623,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 float sacc = 0.f, macc = -__builtin_inff();
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    sacc += S[3][i];
+                    if (!DIRECT) sacc += S[3][i];
                     macc = __builtin_fmaxf(macc, S[3][i]);
                 }
                 ps[3] = sacc;
@@ -623,7 +661,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
             // ---- pseudo-average over all 128 keys of the tile (before masking) ----
             float sbar = 0.f;
-            if (!NAIVE) {
+            if (!NAIVE && !DIRECT) {
                 if (!(EARLY && stats_ready)) {
 #pragma unroll
                     for (int kb = 0; kb < 4; ++kb) {
@@ -676,7 +714,21 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             float g = 1.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
             bool drop = false;    // this row's tile j is too far below the running maximum to matter
             float l_ep = 0.f, l_ec = 1.f;   // l <- l_ep * l + l_ec * l'  (first tile: l = l')
-            if (!STRICT && !NAIVE) {
+            if (DIRECT) {
+                // ordinary online softmax on the level m' + c of this tile's maximum; same bookkeeping as below
+                const float lev = mx + cj;
+                const float mn = __builtin_fmaxf(m, lev);
+                const float dp = m - mn;
+                const float dc = lev - mn;
+                const bool keep = first || unseen;
+                drop = !keep && dc < -60.f;
+                const float g_all = exp_nat((dp + Lc) - dc);
+                g = (keep || drop) ? 1.f : g_all;
+                Lc = first ? 0.f : unseen ? Lc : drop ? dp + Lc : dc;
+                l_ep = first ? 0.f : unseen ? 1.f : exp_nat(dp);
+                l_ec = unseen ? 0.f : first ? 1.f : exp_nat(dc);
+                m = first ? lev : unseen ? m : mn;
+            } else if (!STRICT && !NAIVE) {
                 // Written without branches (the first tile and rows that see nothing of the tile select their values at
                 // the end) so that it stays in one block with the exponentials.
                 // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division by
@@ -827,7 +879,7 @@ template <int D, int VAR, bool CAUSAL, bool INSTR>
 hipError_t launch_fwd(const PasaLaunch& p)
 {
     constexpr int RWG = 256;
-    constexpr int LDS_BYTES = 4 * (T * D * 2);
+    constexpr int LDS_BYTES = 4 * (T * D * 2) + (VAR == PASA_K_DIRECT ? 512 : 0);
     const int nqt = (p.Nq + RWG - 1) / RWG;
     const dim3 grid((unsigned)(nqt * p.Hq * p.B));
     auto kern = pasa_fwd<D, VAR, CAUSAL, INSTR>;
@@ -835,7 +887,8 @@ hipError_t launch_fwd(const PasaLaunch& p)
                                        LDS_BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
-                       (_Float16*)p.o, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s, p.nonfinite_o);
+                       (_Float16*)p.o, (const _Float16*)p.k0, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
+                       p.nonfinite_o);
     return hipGetLastError();
 }
 
@@ -855,6 +908,7 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
         case PASA_K_STRICT16: return launch_fwd_cv<D, PASA_K_STRICT16>(p);
         case PASA_K_NAIVE16: return launch_fwd_cv<D, PASA_K_NAIVE16>(p);
         case PASA_K_S16: return launch_fwd_cv<D, PASA_K_S16>(p);
+        case PASA_K_DIRECT: return launch_fwd_cv<D, PASA_K_DIRECT>(p);
     }
     return hipErrorInvalidValue;
 }
@@ -862,17 +916,17 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 }  // namespace
 
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
-                            int B, int Hkv, int N, int d, double beta, double kscale, int matrix_mode, int in_bf16,
-                            hipStream_t stream)
+                            int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
+                            void* k0out, hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
     const dim3 grid((unsigned)((size_t)B * Hkv * ntile), v != nullptr ? 2u : 1u);   // y: keys / values
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode, in_bf16);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, N, ntile, beta, kscale, matrix_mode, in_bf16);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16);
     return hipGetLastError();
 }
 

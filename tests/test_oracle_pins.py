@@ -475,3 +475,54 @@ def test_bf16_inputs_are_converted_to_fp16_then_the_method_runs():
     got16 = po.pasa_rows(Qh, Kh, Vh, 0.25, True, 0.9375, 128, po.MIXED, 260)
     gotb = po.pasa_rows(Qh, Kh, Vh, 0.25, True, 0.9375, 128, po.MIXED, 260, out_fmt="bf16")
     assert np.abs(gotb - got16.astype(np.float64)).max() <= 2.0 ** -8 * np.abs(got16.astype(np.float64)).max()
+
+
+# ------------------------------------------------------------------ direct-bias recovery (not the paper's step; own name)
+
+def test_direct_recovery_fp64_equals_plain_definition():
+    rng = np.random.default_rng(51)
+    for N, T, causal in ((200, 64, False), (333, 128, True), (128, 128, True)):
+        d = 16
+        Q = rng.standard_normal((N, d)).astype(np.float16)
+        K = (rng.standard_normal((N, d)) * 2 + 6).astype(np.float16)
+        V = rng.standard_normal((N, d)).astype(np.float16)
+        gold = po.attention_fp64(Q, K, V, 0.25, causal)
+        got = po.direct_rows(Q, K, V, 0.25, causal, 0.9375, T, po.EXACT64)
+        # the only rounding left is K' to fp16 (and the fp16 output)
+        assert po.rmse(got, gold) < 2e-3
+        assert np.abs(got.astype(np.float64) - gold).max() < 5e-3
+
+
+def test_direct_shift_identity_and_brute_force():
+    # S' + scale * q.k0 is the true scaled score up to the rounding of K' alone: checked with python floats
+    rng = np.random.default_rng(52)
+    T, d, beta, scale = 8, 4, 0.75, 0.5
+    K = (rng.integers(-8, 9, (2 * T, d)) + 20).astype(np.float16)     # small integers: K' needs no rounding
+    q = rng.integers(-4, 5, d).astype(np.float64)
+    Kp, k0 = po.direct_shift_keys(K, beta, scale, T)
+    for jt in range(2):
+        mean = [sum(float(K[jt * T + n, c]) for n in range(T)) / T for c in range(d)]
+        assert [float(x) for x in k0[jt]] == [float(np.float16(beta * mu)) for mu in mean]
+        for n in range(T):
+            sp = sum(q[c] * float(Kp[jt * T + n, c]) for c in range(d))
+            bias = scale * sum(q[c] * float(k0[jt, c]) for c in range(d))
+            true = scale * sum(q[c] * float(K[jt * T + n, c]) for c in range(d))
+            assert abs(sp + bias - true) < 1e-9
+
+
+def test_direct_recovery_keeps_scores_small_and_is_more_accurate_than_the_amplified_recovery():
+    # large key bias: scores without the shift would overflow fp16; with it they stay small, and adding the bias
+    # back directly avoids the beta/(1-beta) amplification of the rounding noise in Sbar'
+    rng = np.random.default_rng(53)
+    N, d = 512, 64
+    Q = (rng.standard_normal((64, d)) + 3).astype(np.float16)
+    K = (rng.standard_normal((N, d)) * 2 + 40).astype(np.float16)
+    V = rng.standard_normal((N, d)).astype(np.float16)
+    gold = po.attention_fp64(Q, K, V, 0.125, False)
+    info = {}
+    direct = po.direct_rows(Q, K, V, 0.125, False, po.default_beta(), 128, po.MIXED, info=info)
+    paper = po.pasa_rows(Q, K, V, 0.125, False, po.default_beta(), 128, po.MIXED)
+    raw = np.abs(Q.astype(np.float64) @ K.astype(np.float64).T).max()
+    assert raw > 65504 / 8 and info["smax"] < 200
+    assert po.rmse(direct, gold) < 0.5 * po.rmse(paper, gold)
+    assert po.rmse(direct, gold) < 1e-3
