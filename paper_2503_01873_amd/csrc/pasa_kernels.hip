@@ -86,9 +86,12 @@ __device__ inline _Float16 double_to_half_rn(double x)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Pre-processing kernel.  grid = B*Hkv*ceil(N/128) tiles, 256 threads.
+// Pre-processing kernel.  grid = (B*Hkv*ceil(N/128) tiles, work groups of a tile), 256 threads.
 // plain_out != nullptr: write K' in the plain [.., N, D] layout instead (pasa_shift_keys).
 // A ragged last tile is padded with zero keys and zero values in the workspace.
+#ifndef PASA_PREP_SPLIT
+#define PASA_PREP_SPLIT 4
+#endif
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
@@ -97,78 +100,98 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
                                                     int N, int ntile, double beta, double kscale, int shift_mode,
                                                     int in_bf16)
 {
-    constexpr int CH = D / 8;            // 16-byte chunks per key
+    // A tile's work is cut into 2*NS blocks (blockIdx.y): NS groups of D/NS channels of K (column means are per
+    // channel, so the groups are independent) and NS groups of 128/NS keys of V.  The pass is bound by memory
+    // latency and by fp64 arithmetic per thread, not by bandwidth, so it wants many small blocks.
+    constexpr int NS = PASA_PREP_SPLIT;
+    constexpr int DB = D / NS;           // channels of K per block
+    constexpr int CH = DB / 8;           // 16-byte chunks per key within the group
     constexpr int KL = 256 / CH;         // key lanes
     constexpr int KPT = T / KL;          // keys per thread
-    // the two halves of the work (see blockIdx.y below) use the same LDS bytes
-    constexpr size_t PSUM_BYTES = sizeof(double) * KL * D, VS_BYTES = sizeof(_Float16) * T * (D + 8);
+    constexpr int PARTS = 256 / DB;      // second reduction stage: row groups per channel
+    constexpr int TB = T / NS;           // keys of V per block
+    constexpr size_t PSUM_BYTES = sizeof(double) * (KL + PARTS + 1) * DB, VS_BYTES = sizeof(_Float16) * TB * (D + 8);
     __shared__ __attribute__((aligned(16))) char lds_raw[PSUM_BYTES > VS_BYTES ? PSUM_BYTES : VS_BYTES];
-    double (*psum)[D] = reinterpret_cast<double (*)[D]>(lds_raw);
-    _Float16 (*vs)[D + 8] = reinterpret_cast<_Float16 (*)[D + 8]>(lds_raw);   // +8 halfs: rows start 16 bytes apart in bank space
 
     const size_t tile = blockIdx.x;                      // (batch, KV head, key tile)
     const size_t head = tile / ntile;
     const int t = (int)(tile % ntile);
     const int nvalid = (N - t * T) < T ? (N - t * T) : T;    // keys of this tile (< 128 only in a ragged last tile)
     const size_t src_off = (head * (size_t)N + (size_t)t * T) * D;
-    const _Float16* ksrc = k + src_off;
     const int tid = threadIdx.x;
-    const int c8 = tid % CH, kl = tid / CH;
 
-    // blockIdx.y picks the half of the work: 0 shifts the keys, 1 re-tiles the values (twice the blocks in flight
-    // for a pass that is bound by memory latency, not by arithmetic)
-    if (blockIdx.y == 1) {
+    if (blockIdx.y >= NS) {
+        // ---- values: keys [n0, n0 + TB) of the tile, all channels ----
+        _Float16 (*vs)[D + 8] = reinterpret_cast<_Float16 (*)[D + 8]>(lds_raw);   // +8 halfs: rows 16 bytes apart in bank space
+        const int n0 = (blockIdx.y - NS) * TB;
         const _Float16* vsrc = v + src_off;
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const int n = kl + KL * i;
-            *reinterpret_cast<h8*>(&vs[n][8 * c8]) =
-                n < nvalid ? load_h8(vsrc + n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
+        constexpr int VCH = D / 8;
+        for (int idx = tid; idx < TB * VCH; idx += 256) {
+            const int nl = idx / VCH, c8 = idx % VCH, n = n0 + nl;
+            *reinterpret_cast<h8*>(&vs[nl][8 * c8]) =
+                n < nvalid ? load_h8(vsrc + (size_t)n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
         }
         __syncthreads();
         _Float16* vdst = wsout + tile * (size_t)(2 * T * D) + T * D;
-        for (int chunk = tid; chunk < 16 * D; chunk += 256) {
+        const int chunk0 = (n0 / 16) * 2 * D;            // chunk ((n/16)*2 + h)*D + c; this block owns TB/16*2 values of (n/16)*2+h
+        for (int chunk = tid; chunk < (TB / 16) * 2 * D; chunk += 256) {
             const int c = chunk % D;
-            const int kh = chunk / D;            // (n/16)*2 + h
-            const int nb = (kh >> 1) * 16 + (kh & 1) * 4;
+            const int kh = chunk / D;
+            const int nb = (kh >> 1) * 16 + (kh & 1) * 4;    // local key of the first of the 8
             h8 out;
 #pragma unroll
             for (int e = 0; e < 8; ++e) out[e] = vs[nb + (e >> 2) * 8 + (e & 3)][c];
-            *reinterpret_cast<h8*>(vdst + (size_t)chunk * 8) = out;
+            *reinterpret_cast<h8*>(vdst + (size_t)(chunk0 + chunk) * 8) = out;
         }
         return;
     }
+
+    // ---- keys: channels [cg*DB, cg*DB + DB) of the tile, all 128 keys ----
+    double (*psum)[DB] = reinterpret_cast<double (*)[DB]>(lds_raw);              // [KL] partial column sums
+    double (*psum2)[DB] = psum + KL;                                             // [PARTS] second stage
+    double* colv = reinterpret_cast<double*>(psum2 + PARTS);                     // [DB] mean (or sum, or k0) per channel
+    const int cg = blockIdx.y;
+    const int c8 = tid % CH, kl = tid / CH;
+    const int ch0 = cg * DB + 8 * c8;                    // first of this thread's 8 channels
+    const _Float16* ksrc = k + src_off;
 
     h8 kv[KPT];
     double s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
         const int n = kl + KL * i;
-        kv[i] = n < nvalid ? load_h8(ksrc + n * D + 8 * c8, in_bf16) : (h8)(_Float16)0;
+        kv[i] = n < nvalid ? load_h8(ksrc + (size_t)n * D + ch0, in_bf16) : (h8)(_Float16)0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) s[e] += (double)kv[i][e];   // exact: fp16 values, at most 128 terms
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) psum[kl][8 * c8 + e] = s[e];
     __syncthreads();
-
+    {   // every partial sum is exact in fp64, so the order of the two stages does not matter
+        const int c = tid % DB, part = tid / DB;
+        double acc = 0;
+        for (int r = part; r < KL; r += PARTS) acc += psum[r][c];
+        psum2[part][c] = acc;
+    }
+    __syncthreads();
+    if (tid < DB) {
+        double tot = 0;
+#pragma unroll
+        for (int r = 0; r < PARTS; ++r) tot += psum2[r][tid];
+        // the tile's own key count, so that Eq. (14) holds for a ragged tile too; the matrix form needs the plain sum
+        double val = shift_mode == PASA_PREP_MATRIX ? tot : tot / (double)nvalid;
+        // direct-bias recovery: the shift vector k0 = fp16(beta * mean) is itself an fp16 vector
+        if (shift_mode == PASA_PREP_DIRECT) {
+            const _Float16 k0h = double_to_half_rn(__dmul_rn(beta, val));
+            val = (double)k0h;
+            k0out[tile * (size_t)D + cg * DB + tid] = k0h;
+        }
+        colv[tid] = val;
+    }
+    __syncthreads();
     double mean[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        double tot = 0;
-#pragma unroll 4
-        for (int r = 0; r < KL; ++r) tot += psum[r][8 * c8 + e];
-        // the tile's own key count, so that Eq. (14) holds for a ragged tile too; the matrix form needs the plain sum
-        mean[e] = shift_mode == PASA_PREP_MATRIX ? tot : tot / (double)nvalid;
-        // direct-bias recovery: the shift vector k0 = fp16(beta * mean) is itself an fp16 vector
-        if (shift_mode == PASA_PREP_DIRECT) mean[e] = (double)double_to_half_rn(__dmul_rn(beta, mean[e]));
-    }
-    if (shift_mode == PASA_PREP_DIRECT && kl == 0) {
-        h8 k0v;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) k0v[e] = (_Float16)mean[e];      // exact: already an fp16 value
-        *reinterpret_cast<h8*>(k0out + tile * (size_t)D + 8 * c8) = k0v;
-    }
+    for (int e = 0; e < 8; ++e) mean[e] = colv[8 * c8 + e];
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
         const int n = kl + KL * i;
@@ -192,9 +215,9 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
             out[e] = n < nvalid ? double_to_half_rn(r) : (_Float16)0;   // padding keys: exact zeros
         }
         if (plain_out != nullptr) {
-            if (n < nvalid) *reinterpret_cast<h8*>(plain_out + src_off + n * D + 8 * c8) = out;
+            if (n < nvalid) *reinterpret_cast<h8*>(plain_out + src_off + (size_t)n * D + ch0) = out;
         } else {
-            *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)c8 * T + n) * 8) = out;
+            *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)(ch0 / 8) * T + n) * 8) = out;
         }
     }
 }
@@ -920,7 +943,7 @@ hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_
                             void* k0out, hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
-    const dim3 grid((unsigned)((size_t)B * Hkv * ntile), v != nullptr ? 2u : 1u);   // y: keys / values
+    const dim3 grid((unsigned)((size_t)B * Hkv * ntile), (v != nullptr ? 2u : 1u) * PASA_PREP_SPLIT);   // y: key channel groups, then value key groups
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
                            (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16);
