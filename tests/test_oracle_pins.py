@@ -526,3 +526,23 @@ def test_direct_recovery_keeps_scores_small_and_is_more_accurate_than_the_amplif
     assert raw > 65504 / 8 and info["smax"] < 200
     assert po.rmse(direct, gold) < 0.5 * po.rmse(paper, gold)
     assert po.rmse(direct, gold) < 1e-3
+
+
+def test_direct_recovery_reference_is_the_running_maximum_and_ragged_shift_uses_its_own_count():
+    # tile levels 2000 apart: with any reference other than the running maximum an exponential overflows even in fp64
+    rng = np.random.default_rng(54)
+    d, T = 8, 16
+    K = rng.standard_normal((3 * T, d))
+    K[T:2 * T] += 250.0
+    K[2 * T:] -= 250.0
+    K = K.astype(np.float16)
+    Q = np.ones((4, d), np.float16)
+    V = rng.standard_normal((3 * T, d)).astype(np.float16)
+    got = po.direct_rows(Q, K, V, 1.0, False, 0.9375, T, po.EXACT64)
+    gold = po.attention_fp64(Q, K, V, 1.0, False)
+    assert np.isfinite(got).all() and np.abs(got.astype(np.float64) - gold).max() < 5e-3
+    # ragged last tile: its shift vector is beta times the mean over its own keys
+    K2 = np.array([[2, 4], [4, 8], [6, 0], [8, 4], [10, 2], [30, 6]], np.float16)     # T = 4: the tail has 2 keys
+    Kp, k0 = po.direct_shift_keys(K2, 0.5, 1.0, 4)
+    assert np.array_equal(k0.astype(np.float64), [[2.5, 2.0], [10.0, 2.0]])
+    assert np.array_equal(Kp[4:].astype(np.float64), [[0.0, 0.0], [20.0, 4.0]])
