@@ -128,6 +128,18 @@ int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N
 int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
                         float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
 
+/* An adaptive start of PASA (the paper's closing section names it as future work and gives no mechanism; this is
+ * the simplest one).  Pass 1 runs the partially low-precision FlashAttention without any shift (PASA_NAIVE16: raw
+ * scores rounded to fp16, section 2.1) into o and counts in *opts->overflow_s the raw scores that left the fp16
+ * range.  Pass 2 runs opts->variant (not PASA_NAIVE16) into o, but each of its workgroups returns at once unless
+ * that counter is non-zero -- decided on the device, no host synchronisation.  So o holds the unshifted result when
+ * nothing overflowed anywhere in the call, and the PASA result otherwise.  opts and opts->overflow_s (a DEVICE
+ * counter the caller has zeroed; it is the trigger and reports the count) are required, opts->nonfinite_o must be
+ * NULL.  Otherwise the rules of pasa_attn_fwd_ex. */
+int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o,
+                           int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                           const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Key pre-processing alone (Algorithm 1's first loop, Eq. (11)): writes, for every 128-key tile,
  * K'[n, c] = fp16((K[n, c] - beta * mean_tile(K[:, c])) * kscale) to kprime in the plain [B, Hkv, N, d]
  * layout.  The mean and the arithmetic are fp64 and the result is rounded once.  For tests and tools;

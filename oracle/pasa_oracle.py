@@ -453,6 +453,25 @@ def fa_bhnd(q, k, v, scale, causal, T=128, policy=PARTIAL16) -> np.ndarray:
     return out
 
 
+def adaptive_bhnd(q, k, v, scale, causal, beta, T=128, policy=MIXED):
+    """The adaptive start the paper leaves to future work (its closing section), in the simplest form: run the
+    partially low-precision FlashAttention (raw scores stored in fp16, Fig. 2) and keep its result unless some raw
+    score anywhere in the call left the fp16 range; only then run PASA.  Returns (output, triggered)."""
+    B, Hq, N, d = q.shape
+    Hkv = k.shape[1]
+    out = np.empty((B, Hq, N, d), np.float16)
+    overflowed = 0
+    for b in range(B):
+        for h in range(Hq):
+            hk = kv_head(h, Hq, Hkv)
+            info = {}
+            out[b, h] = fa_rows(q[b, h], k[b, hk], v[b, hk], scale, causal, T, PARTIAL16, 0, info)
+            overflowed += info["s_nonfinite"]
+    if overflowed == 0:
+        return out, False
+    return pasa_bhnd(q, k, v, scale, causal, beta, T, policy), True
+
+
 def rmse(o, o_gold) -> float:
     """Relative RMSE, Eq. (19): ||O - O_gold||_2 / ||O_gold||_2."""
     o = np.asarray(o, np.float64)

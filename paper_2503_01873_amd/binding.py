@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
     L.pasa_prepare_kv.restype = ci
     L.pasa_attn_fwd_prepared.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_attn_fwd_prepared.restype = ci
+    L.pasa_attn_fwd_adaptive.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
+    L.pasa_attn_fwd_adaptive.restype = ci
     L.pasa_attn_fwd_chunk.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_attn_fwd_chunk.restype = ci
     L.pasa_shift_keys.argtypes = [vp, vp, ci, ci, ci, ci, cd, cd, vp]
@@ -183,3 +185,14 @@ def pasa_shift_keys_direct(k, kprime, k0, B, Hkv, N, d, beta, kscale, stream=Non
     st = lib().pasa_shift_keys_direct(_ptr(k), _ptr(kprime), _ptr(k0), B, Hkv, N, d, float(beta), float(kscale),
                                       _stream(stream))
     return _check(st, "pasa_shift_keys_direct", check)
+
+
+def pasa_attn_fwd_adaptive(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, workspace, workspace_bytes, stream=None,
+                           beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
+                           shift_mode=SHIFT_MEAN, io_dtype=IO_F16, opts_null=False, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode),
+                     int(io_dtype))
+    st = lib().pasa_attn_fwd_adaptive(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, Hq, Hkv, N, d, int(causal), float(scale),
+                                      None if opts_null else ctypes.byref(opts), _ptr(workspace), int(workspace_bytes),
+                                      _stream(stream))
+    return _check(st, "pasa_attn_fwd_adaptive", check)

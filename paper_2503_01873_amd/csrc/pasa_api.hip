@@ -146,7 +146,7 @@ int shift_keys_common(const void* k, void* kprime, int B, int Hkv, int N, int d,
     if (shift_mode == PASA_PREP_DIRECT && (k0out == nullptr || !aligned(k0out, 16) || k0out == kprime || k0out == k))
         return PASA_EINVAL;
     const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, shift_mode, 0, k0out,
-                                          static_cast<hipStream_t>(stream));
+                                          nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
 
@@ -183,6 +183,7 @@ struct Params {
     float inva;       // beta/(1-beta) rounded to the statistics precision
     unsigned long long* overflow_s;
     unsigned long long* nonfinite_o;
+    const unsigned long long* gate;   // set by the adaptive entry point only
 };
 
 int resolve(const pasa_opts* opts, float scale, Params* out)
@@ -215,6 +216,7 @@ int resolve(const pasa_opts* opts, float scale, Params* out)
     out->inva = op.variant == PASA_STRICT16 ? (float)round_to_format(inva_d, 11, -14, 15) : (float)inva_d;
     out->overflow_s = op.overflow_s;
     out->nonfinite_o = op.nonfinite_o;
+    out->gate = nullptr;
     return PASA_OK;
 }
 
@@ -225,13 +227,18 @@ int check_workspace(const void* ws, size_t bytes, size_t need)
 
 }  // namespace
 
-int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, float scale, const pasa_opts* opts,
-                    void* workspace, size_t workspace_bytes, void* stream)
+}  // extern "C"
+
+namespace {
+
+int prepare_kv_impl(const void* k, const void* v, int B, int Hkv, int N, int d, float scale, const pasa_opts* opts,
+                    void* workspace, size_t workspace_bytes, void* stream, const unsigned long long* gate)
 {
     if (k == nullptr || v == nullptr || !aligned(k, 16) || !aligned(v, 16)) return PASA_EINVAL;
     Params pr;
     int st = resolve(opts, scale, &pr);
     if (st != PASA_OK) return st;
+    pr.gate = gate;
     st = check_shape(B, Hkv, Hkv, N, d);
     if (st != PASA_OK) return st;
     if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;   // M is a full 128 x 128 matrix
@@ -241,8 +248,18 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
     const int mode = pr.variant == PASA_DIRECT ? PASA_PREP_DIRECT : pr.matrix_mode ? PASA_PREP_MATRIX : PASA_PREP_MEAN;
     void* k0out = static_cast<char*>(workspace) + tiles_bytes(B, Hkv, N, d);
     const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, mode, pr.io_bf16,
-                                          k0out, static_cast<hipStream_t>(stream));
+                                          k0out, pr.gate, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, float scale, const pasa_opts* opts,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return prepare_kv_impl(k, v, B, Hkv, N, d, scale, opts, workspace, workspace_bytes, stream, nullptr);
 }
 
 int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
@@ -251,8 +268,13 @@ int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N
     return pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, opts, workspace, workspace_bytes, stream);
 }
 
-int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
-                        float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
+}  // extern "C"
+
+namespace {
+
+int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
+                   float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream,
+                   const unsigned long long* gate)
 {
     if (q == nullptr || o == nullptr || !aligned(q, 16) || !aligned(o, 16) || o == q) return PASA_EINVAL;
     if (causal != 0 && causal != 1) return PASA_EINVAL;
@@ -279,8 +301,57 @@ int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, 
     p.scale = scale;
     p.overflow_s = pr.overflow_s;
     p.nonfinite_o = pr.nonfinite_o;
+    p.gate = gate;
     p.stream = static_cast<hipStream_t>(stream);
     return pasa_launch_fwd(p) == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
+                        float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
+{
+    return fwd_chunk_impl(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, opts, workspace, workspace_bytes, stream,
+                          nullptr);
+}
+
+int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N, int d,
+                           int causal, float scale, const pasa_opts* opts, void* workspace, size_t workspace_bytes,
+                           void* stream)
+{
+    // every check of both passes first, so that nothing is enqueued on error
+    if (q == nullptr || k == nullptr || v == nullptr || o == nullptr) return PASA_EINVAL;
+    if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(o, 16)) return PASA_EINVAL;
+    if (o == q || o == k || o == v) return PASA_EINVAL;
+    if (causal != 0 && causal != 1) return PASA_EINVAL;
+    if (opts == nullptr || opts->overflow_s == nullptr || !aligned(opts->overflow_s, 8)) return PASA_EINVAL;
+    if (opts->nonfinite_o != nullptr || opts->variant == PASA_NAIVE16) return PASA_EINVAL;
+    Params pr;
+    int st = resolve(opts, scale, &pr);
+    if (st != PASA_OK) return st;
+    st = check_shape(B, Hq, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
+    st = check_workspace(workspace, workspace_bytes, pasa_attn_fwd_workspace(B, Hq, Hkv, N, d));
+    if (st != PASA_OK) return st;
+    // pass 1: no shift, raw scores rounded to fp16, counting those that leave the fp16 range
+    pasa_opts first = *opts;
+    first.variant = PASA_NAIVE16;
+    first.shift_mode = PASA_SHIFT_MEAN;
+    first.beta = -1.f;
+    st = prepare_kv_impl(k, v, B, Hkv, N, d, scale, &first, workspace, workspace_bytes, stream, nullptr);
+    if (st != PASA_OK) return st;
+    st = fwd_chunk_impl(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, &first, workspace, workspace_bytes, stream, nullptr);
+    if (st != PASA_OK) return st;
+    // pass 2: the caller's variant, every workgroup leaving at once unless the counter is non-zero
+    pasa_opts second = *opts;
+    second.overflow_s = nullptr;
+    st = prepare_kv_impl(k, v, B, Hkv, N, d, scale, &second, workspace, workspace_bytes, stream, opts->overflow_s);
+    if (st != PASA_OK) return st;
+    return fwd_chunk_impl(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, &second, workspace, workspace_bytes, stream,
+                          opts->overflow_s);
 }
 
 int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N, int d,

@@ -23,19 +23,21 @@ struct PasaLaunch {
     float scale;      // only used by PASA_K_NAIVE16 (static scaling after the first GEMM)
     unsigned long long* overflow_s;
     unsigned long long* nonfinite_o;
+    const unsigned long long* gate;   // non-null: the kernel does nothing unless this device counter is non-zero
     hipStream_t stream;
 };
 
 // Shift + re-tile K (and re-tile V when v != nullptr).  plain_out != nullptr: K' goes there in the
 // plain [B,Hkv,N,d] layout and ws is not written.
 // in_bf16: k and v hold bf16 and are converted to fp16 as they are loaded (outputs stay fp16).
+// gate: non-null: the kernel does nothing unless this device counter is non-zero.
 // PASA_PREP_MEAN:   K' = fp16((K - beta * tile mean) * kscale).
 // PASA_PREP_MATRIX: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
 //                   matrix a I + b (J - I) when beta carries a - b and kscale carries b (N % 128 == 0 only).
 // PASA_PREP_DIRECT: k0 = fp16(beta * tile mean) goes to k0out ([B, Hkv, tiles, d]) and K' = fp16((K - k0) * kscale).
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
-                            void* k0out, hipStream_t stream);
+                            void* k0out, const unsigned long long* gate, hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);
 

@@ -98,8 +98,10 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
                                                     _Float16* __restrict__ wsout,
                                                     _Float16* __restrict__ plain_out, _Float16* __restrict__ k0out,
                                                     int N, int ntile, double beta, double kscale, int shift_mode,
-                                                    int in_bf16)
+                                                    int in_bf16, const unsigned long long* gate)
 {
+    if (gate != nullptr && *gate == 0) return;   // adaptive start: nothing overflowed, the shifted pass is not needed
+
     // A tile's work is cut into 2*NS blocks (blockIdx.y): NS groups of D/NS channels of K (column means are per
     // channel, so the groups are independent) and NS groups of 128/NS keys of V.  The pass is bound by memory
     // latency and by fp64 arithmetic per thread, not by bandwidth, so it wants many small blocks.
@@ -303,8 +305,10 @@ __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
               const _Float16* __restrict__ k0, int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale,
               int io_bf16,
-              unsigned long long* ovf_s, unsigned long long* nonfinite_o)
+              unsigned long long* ovf_s, unsigned long long* nonfinite_o, const unsigned long long* gate)
 {
+    if (gate != nullptr && *gate == 0) return;   // adaptive start: nothing overflowed, the shifted pass is not needed
+
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
     constexpr int CB = D / 32;   // 32-channel row blocks of O^T
     constexpr bool S16 = (VAR != PASA_K_MIXED && VAR != PASA_K_DIRECT);   // S' rounded to fp16 as it leaves the matrix core
@@ -911,7 +915,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
                        (_Float16*)p.o, (const _Float16*)p.k0, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
-                       p.nonfinite_o);
+                       p.nonfinite_o, p.gate);
     return hipGetLastError();
 }
 
@@ -940,16 +944,16 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
-                            void* k0out, hipStream_t stream)
+                            void* k0out, const unsigned long long* gate, hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
     const dim3 grid((unsigned)((size_t)B * Hkv * ntile), (v != nullptr ? 2u : 1u) * PASA_PREP_SPLIT);   // y: key channel groups, then value key groups
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
     return hipGetLastError();
 }
 

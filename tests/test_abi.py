@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     L = P.lib()
     names = _declared_functions()
     assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_workspace", "pasa_prepare_kv",
-            "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_shift_keys_direct",
+            "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_attn_fwd_adaptive", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_shift_keys_direct",
             "pasa_optimal_beta", "pasa_invariance_rounded",
             "pasa_status_string", "pasa_version"} <= set(names)
     for n in names:
@@ -126,6 +126,15 @@ def test_other_entry_points_reject_bad_arguments():
     assert P.pasa_shift_keys_direct(K, O, 0, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_shift_keys_direct(K, O, O, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "N": 200, "shift_mode": P.SHIFT_MATRIX}) == 2
+    ad = dict(B=1, Hq=4, Hkv=2, N=256, d=64, causal=0, scale=0.125, workspace=WS, workspace_bytes=1 << 20, check=False)
+    CNT = 0x60000
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=None, **ad) == 1             # the trigger counter is required
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=CNT, opts_null=True, **ad) == 1
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=CNT, nonfinite_o=CNT + 8, **ad) == 1
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=CNT, variant=P.NAIVE16, **ad) == 1
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=CNT + 4, **ad) == 1           # misaligned counter
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=CNT, **{**ad, "d": 96}) == 2
+    assert P.pasa_attn_fwd_adaptive(Q, K, V, O, overflow_s=CNT, **{**ad, "workspace_bytes": 64}) == 4
     assert P.pasa_prepare_kv(K, V, 1, 2, 256, 64, 0.125, WS, 16, check=False) == 4
     assert P.pasa_prepare_kv(K, 0, 1, 2, 256, 64, 0.125, WS, 1 << 20, check=False) == 1
     assert P.pasa_attn_fwd_prepared(Q, Q, 1, 4, 2, 256, 64, 0, 0.125, WS, 1 << 20, check=False) == 1

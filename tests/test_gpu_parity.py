@@ -550,6 +550,70 @@ def test_seeded_sweep(i, d, N, hkv, g, variant, causal, bias):
         assert c["maxabs"] <= 2e-3
 
 
+# ------------------------------------------------------------------ adaptive start
+
+def _adaptive(q, k, v, causal, scale, variant=P.MIXED):
+    import torch
+    dev = torch.device("cuda:0")
+    B, Hq, N, d = q.shape
+    Hkv = k.shape[1]
+    tq, tk, tv = (torch.from_numpy(np.ascontiguousarray(x)).to(dev) for x in (q, k, v))
+    to = torch.full_like(tq, float("nan"))
+    cnt = torch.zeros(1, dtype=torch.int64, device=dev)
+    wsb = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    P.pasa_attn_fwd_adaptive(tq, tk, tv, to, B, Hq, Hkv, N, d, causal, scale, ws, wsb, torch.cuda.current_stream(),
+                             variant=variant, overflow_s=cnt)
+    torch.cuda.synchronize()
+    return to.cpu().numpy(), int(cnt.item())
+
+
+def test_adaptive_start_keeps_the_unshifted_result_when_nothing_overflows():
+    w = workload(1)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, count = _adaptive(q, k, v, w.causal, scale)
+    plain, _ = gpu_attn(q, k, v, w.causal, scale, P.NAIVE16)
+    ref, trig = po.adaptive_bhnd(q, k, v, scale, w.causal, BETA)
+    assert count == 0 and not trig
+    assert np.array_equal(o.view(np.uint16), plain.view(np.uint16))
+    assert compare(o, ref)["maxabs"] <= 2e-3
+    gold = po.attention_fp64_bhnd(q, k, v, scale, w.causal)
+    r_gpu, r_or = po.rmse(o, gold), po.rmse(ref, gold)
+    assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
+
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.STRICT16, P.DIRECT])
+def test_adaptive_start_switches_to_pasa_on_overflow(variant):
+    w = _small(2, 512, Hq=2, Hkv=1)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, count = _adaptive(q, k, v, w.causal, scale, variant)
+    shifted, _ = gpu_attn(q, k, v, w.causal, scale, variant)
+    assert count > 0 and np.isfinite(o).all()
+    assert np.array_equal(o.view(np.uint16), shifted.view(np.uint16))
+    if variant == P.MIXED:
+        ref, trig = po.adaptive_bhnd(q, k, v, scale, w.causal, BETA)
+        assert trig
+        c = compare(o, ref)
+        assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
+
+
+def test_adaptive_start_one_overflowing_head_is_enough():
+    rng = np.random.default_rng(56)
+    N, d = 384, 128
+    q = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    k = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    v = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    q[0, 1] = 30.0
+    k[0, 1] = 30.0
+    scale = f32(d ** -0.5)
+    o, count = _adaptive(q, k, v, False, scale)
+    ref, trig = po.adaptive_bhnd(q, k, v, scale, False, BETA)
+    assert trig and count == N * N            # every raw score of head 1 is 128 * 900
+    assert np.isfinite(o).all() and compare(o, ref)["maxabs"] <= 2e-3
+
+
 # ------------------------------------------------------------------ capture into a HIP graph
 
 def test_graph_capture_and_replay():

@@ -546,3 +546,20 @@ def test_direct_recovery_reference_is_the_running_maximum_and_ragged_shift_uses_
     Kp, k0 = po.direct_shift_keys(K2, 0.5, 1.0, 4)
     assert np.array_equal(k0.astype(np.float64), [[2.5, 2.0], [10.0, 2.0]])
     assert np.array_equal(Kp[4:].astype(np.float64), [[0.0, 0.0], [20.0, 4.0]])
+
+
+def test_adaptive_start_triggers_exactly_when_a_raw_score_leaves_fp16():
+    rng = np.random.default_rng(55)
+    N, d = 256, 128
+    q = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    k = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    out, trig = po.adaptive_bhnd(q, k, v, 0.088, False, po.default_beta())
+    assert not trig and np.array_equal(out, po.fa_bhnd(q, k, v, 0.088, False, 128, po.PARTIAL16))
+    # the closed form of Table 4's first row: every raw score is 128 * 30^2 = 115200 > 65504 -- in one head only
+    q[0, 1] = 30.0
+    k2 = np.concatenate([k, np.full((1, 1, N, d), 30.0, np.float16)], axis=1)
+    v2 = np.concatenate([v, v], axis=1)
+    out, trig = po.adaptive_bhnd(q, k2, v2, 0.088, False, po.default_beta())
+    assert trig and np.isfinite(out).all()
+    assert np.array_equal(out, po.pasa_bhnd(q, k2, v2, 0.088, False, po.default_beta(), 128, po.MIXED))
