@@ -287,9 +287,8 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 //
 //   group A:  M(0) V(0) M(1) V(1) ...        group B:  -  M(0) V(0) M(1) ...
 //   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]   with, behind the MFMAs of the same wave, the rescale of
-//          the running output (fp32 variants), the row sums / maxima of finished blocks of S'(j) (MIXED), or the fp16
-//          combination of the finished product (STRICT16)
-//   V(j) = [ remaining statistics, exponentials -> P(j), row sum, global recovering scalars ]
+//          the running output (fp32 variants) or the fp16 combination of the finished product (STRICT16)
+//   V(j) = [ row statistics, global recovering scalars, exponentials -> P(j), row sum ]
 //
 // LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued two slots ahead.
 //
@@ -497,13 +496,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     // Hand-offs between the parts of one wave.
     float g_pend = 1.f;              // fp32 variants: factor for the stored output before the pending product is added
-    float ps[4], pm[4];              // partial row sums / maxima of S'(j) taken under the second GEMM (EARLY)
-    bool stats_ready = false;
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) ps[kb] = pm[kb] = 0.f;
-    // MIXED takes the two row reductions of S'(j) while the second GEMM of tile j-1 runs (same wave, co-issued with
-    // its MFMAs) and applies the output rescale under the first GEMM, which shortens the vector part.
-    constexpr bool EARLY = (VAR == PASA_K_MIXED || DIRECT) && !INSTR;
+    // The fp32 variants apply the output rescale behind the MFMAs of the pending product.  The row sums and maxima
+    // of S' are NOT taken behind the first GEMM's MFMAs although they could be: the matrix part is the critical one
+    // of a slot, and with them the kernel measured 3 % slower.
     float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile whose S' was computed last
 
     // Both GEMMs run as one chain of MFMAs per accumulator block (the block index is the slow one), with the LDS
@@ -610,7 +605,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
         }
         // ---- S'(j) ----
-        stats_ready = false;
         if (do_g1) {
             if (STRICT) {
                 // the fp16 combination of the product just finished is folded in behind the MFMAs
@@ -631,31 +625,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         }
                     }
                 });
-            } else if (EARLY && !diag && !tail) {
-                // row sums and maxima of a finished 32-key block are taken behind the MFMAs of the next block
-                gemm1(j, [&](int n) {
-                    const int kb = n / KS - 1, ks = n % KS;
-                    if (kb < 0) return;
-                    constexpr int PER = 16 / KS;
-                    float sacc = ks ? ps[kb] : 0.f, macc = ks ? pm[kb] : -__builtin_inff();
-#pragma unroll
-                    for (int i = ks * PER; i < (ks + 1) * PER; ++i) {
-                        if (!DIRECT) sacc += S[kb][i];
-                        macc = __builtin_fmaxf(macc, S[kb][i]);
-                    }
-                    PASA_PIN2(sacc, macc);
-                    ps[kb] = sacc;
-                    pm[kb] = macc;
-                });
-                float sacc = 0.f, macc = -__builtin_inff();
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    if (!DIRECT) sacc += S[3][i];
-                    macc = __builtin_fmaxf(macc, S[3][i]);
-                }
-                ps[3] = sacc;
-                pm[3] = macc;
-                stats_ready = true;
             } else {
                 gemm1(j, no_hook);
             }
@@ -689,13 +658,12 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             // ---- pseudo-average over all 128 keys of the tile (before masking) ----
             float sbar = 0.f;
             if (!NAIVE && !DIRECT) {
-                if (!(EARLY && stats_ready)) {
+                float ps[4];
 #pragma unroll
-                    for (int kb = 0; kb < 4; ++kb) {
-                        ps[kb] = S[kb][0];
+                for (int kb = 0; kb < 4; ++kb) {
+                    ps[kb] = S[kb][0];
 #pragma unroll
-                        for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
-                    }
+                    for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
                 }
                 // padding keys of a ragged last tile have K' = 0 and add nothing; the divisor is the tile's own key count
                 const float sum = sum32((ps[0] + ps[1]) + (ps[2] + ps[3]));
@@ -715,13 +683,12 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     }
             }
             // ---- local maximum m' ----
-            if (!(EARLY && stats_ready)) {
+            float pm[4];
 #pragma unroll
-                for (int kb = 0; kb < 4; ++kb) {
-                    pm[kb] = S[kb][0];
+            for (int kb = 0; kb < 4; ++kb) {
+                pm[kb] = S[kb][0];
 #pragma unroll
-                    for (int i = 1; i < 16; ++i) pm[kb] = __builtin_fmaxf(pm[kb], S[kb][i]);
-                }
+                for (int i = 1; i < 16; ++i) pm[kb] = __builtin_fmaxf(pm[kb], S[kb][i]);
             }
             const float mx = max32(__builtin_fmaxf(__builtin_fmaxf(pm[0], pm[1]), __builtin_fmaxf(pm[2], pm[3])));
             // A wave whose rows straddle a tile boundary (chunks not aligned to 32 rows) reaches tile j although its
