@@ -290,7 +290,8 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 //          the running output (fp32 variants) or the fp16 combination of the finished product (STRICT16)
 //   V(j) = [ row statistics, global recovering scalars, exponentials -> P(j), row sum ]
 //
-// LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued two slots ahead.
+// LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued from the vector parts,
+// one to two slots before the first matrix part that reads them.
 //
 // Output accumulation.  STRICT16 keeps Algorithm 1's form: the tile product is rounded to fp16 and combined as
 // O = fp16(e^{dm_j} * PV) + fp16(e^{dm_{j-1}} * O).  The fp32 variants accumulate the second GEMM directly onto the
@@ -485,8 +486,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     auto drain_copies = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };   // vmcnt(0)
 
     // Barrier b ends slot b-1 and starts slot b.  Group A runs M(j) in slot 2j and V(j) in slot 2j+1; group B runs
-    // M(j) in slot 2j+1 and V(j) in slot 2j+2.  Copies are issued at the start of every even slot by all waves and
-    // drained by their issuers before the barrier that starts the slot two later.
+    // M(j) in slot 2j+1 and V(j) in slot 2j+2.  Every wave issues its share of the copies K'(j+1), V(j) from its
+    // vector part V(j) for group A (slot 2j+1) and V(j-1) for group B (slot 2j) -- the matrix part is the critical one
+    // and stays free of them -- and drains them before the barrier that starts slot 2j+2, when group A reads them.
     drain_copies();
     __syncthreads();                       // barrier 0: K'(0) is in LDS
     if (grp == 1) {
@@ -542,7 +544,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             PASA_FENCE();
             hook(n);
             if (n + PF < NM1) a[n % PF] = frag(n + PF);
-            if (grp == 0 && (n % (NM1 / CPW)) == NM1 / CPW - 1) issue_copy(2 * jt, CPW + n / (NM1 / CPW));
             PASA_FENCE();
         }
     };
@@ -563,7 +564,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             PASA_FENCE();
             hook(n);
             if (n + PF < NM2) a[n % PF] = frag(n + PF);
-            if (grp == 0 && (n % (NM2 / CPW)) == NM2 / CPW - 1) issue_copy(2 * (jt + 1), n / (NM2 / CPW));
             PASA_FENCE();
         }
     };
@@ -574,16 +574,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
         const bool tail = (tail_keys != 0) && (j == ntile - 1); // ragged last tile: padding keys are masked
         const bool diag = (CAUSAL && (j * T + T - 1 > pos_w0)) || tail;   // tile j needs the mask for this wave
-        if (grp == 0) {   // group A spreads its copies over the GEMM steps; whatever has no GEMM to hide behind goes now
-            if (!do_g2) {
-#pragma unroll
-                for (int idx = 0; idx < CPW; ++idx) issue_copy(2 * j, idx);
-            }
-            if (!do_g1) {
-#pragma unroll
-                for (int idx = CPW; idx < 2 * CPW; ++idx) issue_copy(2 * j, idx);
-            }
-        }
         __builtin_amdgcn_s_setprio(1);
         // ---- pending product of tile j-1 ----
         if (do_g2) {
@@ -632,7 +622,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         __builtin_amdgcn_s_setprio(0);
         if (grp == 1) drain_copies();
         __syncthreads();
-        if (grp == 1 && !(j < J_w)) issue_slot(2 * j + 2);   // no vector part to spread them over
+        const int sg_mine = grp ? 2 * j + 2 : 2 * j;          // the even slot whose copies this wave issues now
+        if (!(j < J_w)) issue_slot(sg_mine);                  // no vector part to spread them over
 
         // =========================== vector part V(j) ===========================
         if (j < J_w) {
@@ -768,10 +759,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
                         pl[kb] = add_pair(p2, pl[kb]);
                     }
-                    if (grp == 1) {   // group B spreads its copies over the exponentials
+                    {   // the copies are spread over the exponentials
                         PASA_FENCE();
 #pragma unroll
-                        for (int idx = kb * (2 * CPW) / 4; idx < (kb + 1) * (2 * CPW) / 4; ++idx) issue_copy(2 * j + 2, idx);
+                        for (int idx = kb * (2 * CPW) / 4; idx < (kb + 1) * (2 * CPW) / 4; ++idx) issue_copy(sg_mine, idx);
                         PASA_FENCE();
                     }
                 }
