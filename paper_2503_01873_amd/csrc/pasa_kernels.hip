@@ -498,9 +498,14 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     // Hand-offs between the parts of one wave.
     float g_pend = 1.f;              // fp32 variants: factor for the stored output before the pending product is added
-    // The fp32 variants apply the output rescale behind the MFMAs of the pending product.  The row sums and maxima
-    // of S' are NOT taken behind the first GEMM's MFMAs although they could be: the matrix part is the critical one
-    // of a slot, and with them the kernel measured 3 % slower.
+    // The fp32 variants apply the output rescale behind the MFMAs of the pending product.  Of the row statistics of
+    // S' only the maxima of the first three key blocks are taken behind the first GEMM's MFMAs (MIXED, DIRECT; not on
+    // tiles that need the mask): the exponentials wait for the maximum, so this shortens the vector part's critical
+    // path (1.8 %).  The row sums stay in the vector part: hooked as well they made the matrix part, which is the
+    // longer part of a slot, longer still (3 % slower).
+    constexpr bool EARLY_MAX = (VAR == PASA_K_MIXED || DIRECT) && !INSTR;
+    float epm[3] = {0.f, 0.f, 0.f};  // maxima of key blocks 0-2 of S'(j), handed from the matrix to the vector part
+    bool max_ready = false;
     float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile whose S' was computed last
 
     // Both GEMMs run as one chain of MFMAs per accumulator block (the block index is the slow one), with the LDS
@@ -615,7 +620,20 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         }
                     }
                 });
+            } else if (EARLY_MAX && !diag && !tail) {
+                gemm1(j, [&](int n) {      // the maximum of a finished 32-key block behind the MFMAs of the next one
+                    const int kb = n / KS - 1, ks = n % KS;
+                    if (kb < 0) return;
+                    constexpr int PER = 16 / KS;
+                    float macc = ks ? epm[kb] : -__builtin_inff();
+#pragma unroll
+                    for (int i = ks * PER; i < (ks + 1) * PER; ++i) macc = __builtin_fmaxf(macc, S[kb][i]);
+                    asm volatile("" : "+v"(macc));    // stays behind this MFMA (see PASA_PIN2)
+                    epm[kb] = macc;
+                });
+                max_ready = true;
             } else {
+                max_ready = false;
                 gemm1(j, no_hook);
             }
         }
@@ -677,6 +695,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             float pm[4];
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) {
+                if (EARLY_MAX && kb < 3 && max_ready) {
+                    pm[kb] = epm[kb];
+                    continue;
+                }
                 pm[kb] = S[kb][0];
 #pragma unroll
                 for (int i = 1; i < 16; ++i) pm[kb] = __builtin_fmaxf(pm[kb], S[kb][i]);
