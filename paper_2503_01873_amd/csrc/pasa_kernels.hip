@@ -438,13 +438,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
                 const h2 ot = pack_rn(O[cb][2 * t], O[cb][2 * t + 1]);
-                if (jt == 0) {
-                    O16[cb][t] = ot;
-                } else {
-                    const h2 a1 = ec2 * ot;               // each packed op rounds to fp16 once
-                    const h2 a2 = ep2 * O16[cb][t];
-                    O16[cb][t] = a1 + a2;
-                }
+                const h2 a1 = ec2 * ot;                   // each packed op rounds to fp16 once; first tile: 1 * ot + 0 * 0
+                const h2 a2 = ep2 * O16[cb][t];
+                O16[cb][t] = a1 + a2;
             }
     };
 
@@ -602,24 +598,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         // ---- S'(j) ----
         if (do_g1) {
             if (STRICT) {
-                // the fp16 combination of the product just finished is folded in behind the MFMAs
-                gemm1(j, [&](int n) {
-                    if (!do_g2) return;
-                    const _Float16 ec = (_Float16)ec_s, ep = (_Float16)ep_s;
-                    const h2 ec2 = {ec, ec}, ep2 = {ep, ep};
-#pragma unroll
-                    for (int e = 0; e < (CB * 8) / NM1; ++e) {
-                        const int item = n * ((CB * 8) / NM1) + e, cb = item >> 3, t = item & 7;
-                        const h2 ot = pack_rn(O[cb][2 * t], O[cb][2 * t + 1]);
-                        if (j == 1) {
-                            O16[cb][t] = ot;
-                        } else {
-                            const h2 a1 = ec2 * ot;               // each packed op rounds to fp16 once
-                            const h2 a2 = ep2 * O16[cb][t];
-                            O16[cb][t] = a1 + a2;
-                        }
-                    }
-                });
+                // the fp16 combination of the product just finished is left to the vector part: hooked behind these
+                // MFMAs it made the matrix part, the longer part of a slot, longer
+                gemm1(j, no_hook);
             } else if (EARLY_MAX && !diag && !tail) {
                 gemm1(j, [&](int n) {      // the maximum of a finished 32-key block behind the MFMAs of the next one
                     const int kb = n / KS - 1, ks = n % KS;
@@ -646,8 +627,22 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         // =========================== vector part V(j) ===========================
         if (j < J_w) {
             const bool first = (j == 0);
+            if (STRICT && do_g2) fold16(j - 1);      // O <- fp16(e^{dm_j} PV) + fp16(e^{dm_{j-1}} O) for the product of tile j-1
             // ---- S' as stored: fp32, or rounded to fp16 ----
-            if (S16) {
+            // STRICT16 keeps the rounded scores packed two per register and works on them with packed fp16
+            // instructions (same roundings, half the instructions and registers)
+            h2 Sh[4][8];
+            if (STRICT) {
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) {
+                        if (INSTR)
+                            n_ovf += ((__builtin_fabsf(S[kb][2 * t]) >= 65520.f) ? 1u : 0u) +
+                                     ((__builtin_fabsf(S[kb][2 * t + 1]) >= 65520.f) ? 1u : 0u);
+                        Sh[kb][t] = pack_rn(S[kb][2 * t], S[kb][2 * t + 1]);
+                    }
+            } else if (S16) {
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
@@ -670,6 +665,12 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 float ps[4];
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
+                    if (STRICT) {          // fp16 values summed in fp32
+                        ps[kb] = 0.f;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) ps[kb] = add_pair(Sh[kb][t], ps[kb]);
+                        continue;
+                    }
                     ps[kb] = S[kb][0];
 #pragma unroll
                     for (int i = 1; i < 16; ++i) ps[kb] += S[kb][i];
@@ -688,7 +689,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = j * T + 32 * kb + 8 * (i >> 2) + 4 * lh + (i & 3);
-                        if (key > last_key) S[kb][i] = -__builtin_inff();
+                        if (key > last_key) {
+                            if (STRICT) Sh[kb][i >> 1][i & 1] = (_Float16)(-__builtin_inff());
+                            else S[kb][i] = -__builtin_inff();
+                        }
                     }
             }
             // ---- local maximum m' ----
@@ -697,6 +701,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             for (int kb = 0; kb < 4; ++kb) {
                 if (EARLY_MAX && kb < 3 && max_ready) {
                     pm[kb] = epm[kb];
+                    continue;
+                }
+                if (STRICT) {
+                    h2 mm = Sh[kb][0];
+#pragma unroll
+                    for (int t = 1; t < 8; ++t) mm = __builtin_elementwise_max(mm, Sh[kb][t]);
+                    pm[kb] = __builtin_fmaxf((float)mm[0], (float)mm[1]);
                     continue;
                 }
                 pm[kb] = S[kb][0];
@@ -721,7 +732,29 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             float g = 1.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
             bool drop = false;    // this row's tile j is too far below the running maximum to matter
             float l_ep = 0.f, l_ec = 1.f;   // l <- l_ep * l + l_ec * l'  (first tile: l = l')
-            if (DIRECT) {
+            bool l_keep = false;             // STRICT16: this row's state is not touched by this tile
+            if (STRICT) {
+                // Step 3 with every operation rounded to fp16, in the order Algorithm 1 states them; computed before
+                // the exponentials and without branches (the first tile and rows that see nothing of the tile select
+                // their values at the end) so that the latency of this chain is hidden.  The factors of the output
+                // combination go to ep_s / ec_s (the pending product of tile j-1 has been folded in above).
+                const _Float16 jm1 = (_Float16)(float)j, jn = (_Float16)(float)(j + 1);
+                const _Float16 Fo = (_Float16)F, sb = (_Float16)sbar, mo = (_Float16)m, mxh = (_Float16)mx;
+                const _Float16 iv = (_Float16)inva;
+                const _Float16 Fn = (_Float16)((_Float16)((_Float16)(jm1 * Fo) + sb) / jn);
+                const _Float16 dpp = (_Float16)(iv * (_Float16)(Fo - Fn));
+                const _Float16 dpc = (_Float16)(iv * (_Float16)(sb - Fn));
+                const _Float16 c1 = (_Float16)(mo + dpp), c2 = (_Float16)(mxh + dpc);
+                const _Float16 mn = c1 > c2 ? c1 : c2;
+                const _Float16 dp = (_Float16)((_Float16)(mo - mn) + dpp);
+                const _Float16 dc = (_Float16)((_Float16)(mxh - mn) + dpc);
+                const _Float16 ep = (_Float16)exp_nat((float)dp), ec = (_Float16)exp_nat((float)dc);
+                l_keep = unseen;
+                F = first ? sbar : unseen ? F : (float)Fn;
+                m = first ? mx : unseen ? m : (float)mn;
+                ep_s = first ? 0.f : unseen ? 1.f : (float)ep;     // unseen: O <- fp16(0 * 0) + fp16(1 * O)
+                ec_s = first ? 1.f : unseen ? 0.f : (float)ec;
+            } else if (DIRECT) {
                 // ordinary online softmax on the level m' + c of this tile's maximum; same bookkeeping as below
                 const float lev = mx + cj;
                 const float mn = __builtin_fmaxf(m, lev);
@@ -770,8 +803,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     for (int t2 = 0; t2 < 8; ++t2) {
                         float e0, e1;
                         if (STRICT) {   // the difference is itself rounded to fp16 before the exponential
-                            e0 = exp_nat((float)(_Float16)(S[kb][2 * t2] - mref));
-                            e1 = exp_nat((float)(_Float16)(S[kb][2 * t2 + 1] - mref));
+                            const _Float16 mh = (_Float16)mref;      // exact: m' is one of the fp16 scores (or 0)
+                            const h2 d2 = Sh[kb][t2] - (h2){mh, mh};
+                            e0 = exp_nat((float)d2[0]);
+                            e1 = exp_nat((float)d2[1]);
                         } else {        // exp(s - m) = 2^(s*log2e - m*log2e), one fused multiply-add per element
                             e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][2 * t2], LOG2E, nml));
                             e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][2 * t2 + 1], LOG2E, nml));
@@ -798,34 +833,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 g = e_old;
             } else if (!STRICT) {
                 l = first ? lsum : l_ep * l + l_ec * lsum;
-            } else if (first) {
-                F = sbar;
-                m = mx;
-                l = lsum;
-                ec_s = 1.f;
-                ep_s = 0.f;
-            } else if (unseen) {      // O <- fp16(0 * 0) + fp16(1 * O)
-                ec_s = 0.f;
-                ep_s = 1.f;
             } else {
-                // every operation rounded to fp16, in the order Algorithm 1 states them
-                const _Float16 jm1 = (_Float16)(float)j, jn = (_Float16)(float)(j + 1);
-                const _Float16 Fo = (_Float16)F, sb = (_Float16)sbar, mo = (_Float16)m, mxh = (_Float16)mx;
-                const _Float16 iv = (_Float16)inva;
-                const _Float16 Fn = (_Float16)((_Float16)((_Float16)(jm1 * Fo) + sb) / jn);
-                const _Float16 dpp = (_Float16)(iv * (_Float16)(Fo - Fn));
-                const _Float16 dpc = (_Float16)(iv * (_Float16)(sb - Fn));
-                const _Float16 c1 = (_Float16)(mo + dpp), c2 = (_Float16)(mxh + dpc);
-                const _Float16 mn = c1 > c2 ? c1 : c2;
-                const _Float16 dp = (_Float16)((_Float16)(mo - mn) + dpp);
-                const _Float16 dc = (_Float16)((_Float16)(mxh - mn) + dpc);
-                const _Float16 ep = (_Float16)exp_nat((float)dp), ec = (_Float16)exp_nat((float)dc);
+                // fp16, each operation rounded: l = fp16(fp16(e^{dm_{j-1}} l) + fp16(e^{dm_j} l')); first tile: l = l'
                 const _Float16 lo = (_Float16)l, ln = (_Float16)lsum;
-                l = (float)(_Float16)((_Float16)(ep * lo) + (_Float16)(ec * ln));
-                F = (float)Fn;
-                m = (float)mn;
-                ep_s = (float)ep;
-                ec_s = (float)ec;
+                const float ln_all = (float)(_Float16)((_Float16)((_Float16)ep_s * lo) + (_Float16)((_Float16)ec_s * ln));
+                l = first ? lsum : l_keep ? l : ln_all;
             }
             if (!STRICT) {
                 if (__builtin_amdgcn_ballot_w64(drop) != 0ull) {
