@@ -83,8 +83,11 @@ def cpu_baseline(w, q_heads, kv_heads, scale, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--settle-ms", type=float, default=500.0,
+                    help="before the warmup steps, run untimed steps for this long: an idle GPU takes some hundred "
+                         "steps of this size to reach its sustained clock, and steps timed before that run 9 %% slower")
     ap.add_argument("--variant", default="mixed", choices=["mixed", "strict16", "s16", "naive16", "direct"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
@@ -135,6 +138,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    settle_steps = 0
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        settle_steps += 20
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -157,6 +167,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_steps": settle_steps,
         "ms_per_step": ms_per_step,
         "higher_is_better": True,
         "scaling": "weak",
