@@ -295,11 +295,21 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 //
 // Output accumulation.  STRICT16 keeps Algorithm 1's form: the tile product is rounded to fp16 and combined as
 // O = fp16(e^{dm_j} * PV) + fp16(e^{dm_{j-1}} * O).  The fp32 variants accumulate the second GEMM directly onto the
-// running output, which is stored relative to the level of the tile that was added last: with c_j = e^{dm_j},
-// O_j = c_j * Ostore_j and Ostore_j = P_j V_j + g_j * Ostore_{j-1}, g_j = e^{dm_{j-1}} * c_{j-1} / c_j.  P_j itself is
-// the paper's exp(S' - m'_j) rounded to fp16, so the GEMM operands are those of Algorithm 1 and only fp32 rounding
-// order differs.  A tile whose level lies more than 60 below the running maximum cannot change an fp32 output
-// and is dropped for that row (P row zeroed), which keeps g_j <= e^60.
+// running output, which is stored at a scale of its own: O_j = e^{Lc_j} * Ostore_j.
+//  * MIXED and S16 leave the stored output alone and give the tile's P the factor instead: with dp = dm_{j-1} and
+//    dc = dm_j of Algorithm 1's step 3, Lc_j = Lc_{j-1} + dp and P_j = fp16(exp(S' - m'_j + c_j)), c_j = dc - Lc_j, so
+//    Ostore_j = Ostore_{j-1} + P_j V_j and the running sum l is kept at the same scale (l += rowsum(P_j); the final
+//    quotient needs no factor).  c_j is the tile's level relative to the stored scale, which is the level of an earlier
+//    tile: c_j <= 0 unless the running maximum rises.  Only when c_j > 8 is a row's stored output and sum multiplied
+//    by e^{-c_j} (then Lc_j = dc, c_j = 0), a branch taken on a few tiles at the start of a row at most; so P <= e^8,
+//    far inside fp16, and a tile far below the running maximum underflows to zero by itself.  This removes the 64
+//    multiplications per tile and lane of a per-tile rescale and three exponentials from the recovering scalars
+//    (3.7 % of the kernel time); the price is that P is Algorithm 1's exp(S' - m') times e^{c_j} rounded once, not
+//    exp(S' - m') rounded and then scaled, so outputs agree with a step-by-step evaluation to rounding, not bit for bit.
+//  * DIRECT and NAIVE16 rescale the stored output on every tile behind the MFMAs of the second GEMM (Lc_j = dc,
+//    Ostore_j = P_j V_j + g_j * Ostore_{j-1}, g_j = e^{dp + Lc_{j-1} - dc}, P_j = fp16(exp(S' - m'_j)) as printed); a
+//    tile whose level lies more than 60 below the running maximum cannot change an fp32 output and is dropped for that
+//    row (P row zeroed), which keeps g_j <= e^60.
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
@@ -493,8 +503,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     }
 
     // Hand-offs between the parts of one wave.
-    float g_pend = 1.f;              // fp32 variants: factor for the stored output before the pending product is added
-    // The fp32 variants apply the output rescale behind the MFMAs of the pending product.  Of the row statistics of
+    float g_pend = 1.f;              // DIRECT, NAIVE16: factor for the stored output before the pending product is added
+    constexpr bool LAZY = (VAR == PASA_K_MIXED || VAR == PASA_K_S16);   // the factor goes to P, not to the stored output
+    constexpr float CMAX = 8.f;      // LAZY: P may exceed 1 by at most e^CMAX before the row re-references its scale
+    // DIRECT and NAIVE16 apply the output rescale behind the MFMAs of the pending product.  Of the row statistics of
     // S' only the maxima of the first three key blocks are taken behind the first GEMM's MFMAs (MIXED, DIRECT; not on
     // tiles that need the mask): the exponentials wait for the maximum, so this shortens the vector part's critical
     // path (1.8 %).  The row sums stay in the vector part: hooked as well they made the matrix part, which is the
@@ -578,7 +590,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         __builtin_amdgcn_s_setprio(1);
         // ---- pending product of tile j-1 ----
         if (do_g2) {
-            if (STRICT) {
+            if (STRICT || LAZY) {
                 gemm2(j - 1, no_hook);
             } else {
                 // the stored output takes its factor block by block, one block ahead of the MFMA chain that adds to it
@@ -726,12 +738,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 m = mnew;
                 mref = mnew;
             }
-            // ---- fp32 variants: global recovering (step 3) and the output rescale factor now, before the exponentials.
-            // Only the running sum needs l'; the rest is a chain of some forty dependent scalar operations whose
+            // ---- fp32 variants: global recovering (step 3) and the factor of the output or of P now, before the
+            // exponentials.  Only the running sum needs l'; the rest is a chain of dependent scalar operations whose
             // latency is hidden when the exponentials that follow can issue in between. ----
-            float g = 1.f;        // factor for the stored output before tile j is accumulated (fp32 variants)
-            bool drop = false;    // this row's tile j is too far below the running maximum to matter
-            float l_ep = 0.f, l_ec = 1.f;   // l <- l_ep * l + l_ec * l'  (first tile: l = l')
+            float g = 1.f;        // DIRECT, NAIVE16: factor for the stored output before tile j is accumulated
+            bool drop = false;    // DIRECT: this row's tile j is too far below the running maximum to matter
+            float l_ep = 0.f, l_ec = 1.f;   // DIRECT: l <- l_ep * l + l_ec * l'  (first tile: l = l')
+            float c_adj = 0.f;    // LAZY: log of the factor this tile's P carries (its level relative to the stored scale)
+            bool resc = false;    // LAZY: this row re-references its stored output and sum to the level of tile j
+            float lc_resc = 0.f;  // LAZY: log of the factor that does it
             bool l_keep = false;             // STRICT16: this row's state is not touched by this tile
             if (STRICT) {
                 // Step 3 with every operation rounded to fp16, in the order Algorithm 1 states them; computed before
@@ -772,8 +787,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 // Written without branches (the first tile and rows that see nothing of the tile select their values at
                 // the end) so that it stays in one block with the exponentials.
                 // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division by
-                // j is a multiplication by 1/j here
-                const float jm1 = (float)j, rj = 1.0f / (float)(j + 1);
+                // j is a multiplication by the hardware's reciprocal of j here
+                const float jm1 = (float)j, rj = __builtin_amdgcn_rcpf((float)(j + 1));
                 const float Fn = (jm1 * F + sbar) * rj;
                 const float dpp = inva * (F - Fn);
                 const float dpc = inva * (sbar - Fn);
@@ -781,20 +796,31 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 const float dp = (m - mn) + dpp;
                 const float dc = (mx - mn) + dpc;
                 const bool keep = first || unseen;        // no recovering step for this row
-                drop = !keep && dc < -60.f;
-                // dropped: O_j = e^{dp} O_{j-1}, same stored output at a smaller scale; else the stored output is rescaled
-                const float g_all = exp_nat((dp + Lc) - dc);
-                g = (keep || drop) ? 1.f : g_all;
-                Lc = first ? 0.f : unseen ? Lc : drop ? dp + Lc : dc;
-                l_ep = first ? 0.f : unseen ? 1.f : exp_nat(dp);
-                l_ec = unseen ? 0.f : first ? 1.f : exp_nat(dc);
+                // the stored output keeps its scale (its log moves by dp with the frame); the tile's P takes the factor
+                // e^c that places it there, unless that is too large: then the row's output and sum move to this tile
+                const float lcn = Lc + dp, c = dc - lcn;
+                resc = !keep && c > CMAX;
+                lc_resc = -c;
+                c_adj = (keep || resc) ? 0.f : c;
+                Lc = first ? 0.f : unseen ? Lc : resc ? dc : lcn;
                 F = first ? sbar : unseen ? F : Fn;
                 m = first ? mx : unseen ? m : mn;
             }
-            // ---- P = exp(S' - m') rounded to fp16; l' = sum of the rounded P ----
+            if (LAZY && __builtin_amdgcn_ballot_w64(resc) != 0ull) {
+                // rare (the running maximum rose by more than CMAX above the stored scale); the pending product of
+                // tile j-1 is already in O.  The empty asm keeps this a branch instead of 64 selects on every tile.
+                asm volatile("" ::: "memory");
+                const float r = resc ? exp_nat(lc_resc) : 1.f;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) O[cb][i] *= r;
+                l *= r;
+            }
+            // ---- P = exp(S' - m' [+ c]) rounded to fp16; l' = sum of the rounded P ----
             float lsum;
             {
-                const float nml = -mref * LOG2E;
+                const float nml = (c_adj - mref) * LOG2E;
                 float pl[4];
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
@@ -831,6 +857,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             if (NAIVE) {
                 l = e_old * l + lsum;
                 g = e_old;
+            } else if (LAZY) {
+                l += lsum;                     // the sum is kept at the stored output's scale (first tile: l was 0)
             } else if (!STRICT) {
                 l = first ? lsum : l_ep * l + l_ec * lsum;
             } else {
@@ -839,7 +867,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 const float ln_all = (float)(_Float16)((_Float16)((_Float16)ep_s * lo) + (_Float16)((_Float16)ec_s * ln));
                 l = first ? lsum : l_keep ? l : ln_all;
             }
-            if (!STRICT) {
+            if (!STRICT && !LAZY) {
                 if (__builtin_amdgcn_ballot_w64(drop) != 0ull) {
                     // rare; the empty asm keeps the compiler from turning this branch into 32 selects on every tile
                     asm volatile("" ::: "memory");
@@ -859,7 +887,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     unsigned long long n_bad = 0;
     if (wave_valid) {
         if (STRICT) fold16(J_w - 1);
-        const float oscale = STRICT ? 0.f : exp_nat(Lc) / l;
+        const float oscale = STRICT ? 0.f : LAZY ? 1.0f / l : exp_nat(Lc) / l;
         _Float16* obase = o + ((size_t)(b * Hq + hq) * Nq) * D;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)

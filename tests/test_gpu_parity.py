@@ -331,7 +331,10 @@ def test_bf16_io(idx, N, over, variant):
         assert c["maxabs"] <= 4e-3
     else:
         assert c["p999"] <= 4e-3 and c["maxabs"] <= 1.6e-2
-    assert (o == ref).mean() > (0.9 if variant == P.MIXED else 0.6)
+    # Sanity only: most outputs round to the same bf16 value.  The kernel's P carries the factor that places the tile at
+    # the stored output's scale (folded into the exponent), so its fp16 rounding differs from the oracle's P of
+    # Algorithm 1 and the outputs agree to rounding, not bit for bit.
+    assert (o == ref).mean() > (0.85 if variant == P.MIXED else 0.6)
 
 
 def test_bf16_input_beyond_fp16_range_becomes_infinite_like_the_oracle():
@@ -548,6 +551,43 @@ def test_seeded_sweep(i, d, N, hkv, g, variant, causal, bias):
         assert c["p99"] <= 4e-3
     else:
         assert c["maxabs"] <= 2e-3
+
+
+# ------------------------------------------------------------------ score level moving from tile to tile
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.DIRECT, P.STRICT16])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("step", [3.0, -3.0, 12.0])
+def test_score_level_staircase(step, causal, variant):
+    """The level of the scores moves by `step` from one key tile to the next (by more for some rows, less for others).
+    Rising, the running maximum leaves the scale the output is stored at behind by more than e^8 every few tiles
+    (step 3) or on every tile (step 12), which takes the kernel's rare re-scaling path of the stored output; falling,
+    later tiles sink far below it and their probabilities underflow."""
+    rng = np.random.default_rng(4242)
+    d, N, T = 64, 1100, 128
+    u = np.zeros(d)
+    u[5] = 1.0
+    qf = rng.standard_normal((1, 2, N, d)) + 4.0 * u
+    tile = np.arange(N) // T
+    kf = rng.standard_normal((1, 1, N, d)) + (2.0 * step * tile)[None, None, :, None] * u
+    q, k = qf.astype(np.float16), kf.astype(np.float16)
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    scale = f32(0.125)
+    o, cnt = gpu_attn(q, k, v, causal, scale, variant, counters=True)
+    if variant == P.DIRECT:
+        ref = po.direct_bhnd(q, k, v, scale, causal, BETA, 128, po.MIXED)
+    else:
+        ref = po.pasa_bhnd(q, k, v, scale, causal, BETA, 128, ORACLE_POLICY[variant])
+    gold = po.attention_fp64_bhnd(q, k, v, scale, causal)
+    c = compare(o, ref)
+    r_gpu, r_or = po.rmse(o, gold), po.rmse(ref, gold)
+    print(VARIANT_NAME[variant], step, causal, c, "rmse gpu %.3e oracle %.3e" % (r_gpu, r_or))
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    if variant == P.STRICT16:      # fp16 statistics: the weights of whole tiles differ by fp16 roundings times 63.5
+        assert c["p99"] <= 8e-3 and abs(r_gpu - r_or) <= 0.1 * r_or + 1e-4
+    else:
+        assert c["maxabs"] <= 2e-3
+        assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
 
 
 # ------------------------------------------------------------------ adaptive start
