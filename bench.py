@@ -156,7 +156,9 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt * 1e3 / args.steps
-    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    kern_all = np.array([a.elapsed_time(b) for a, b in events])
+    kern_ms = float(kern_all.mean())
+    prop = torch.cuda.get_device_properties(dev)
     tflops = w.flops / (ms_per_step * 1e-3) / 1e12
     kern_tflops = w.flops / (kern_ms * 1e-3) / 1e12
 
@@ -180,7 +182,10 @@ def main():
         "frac_of_fp16_mfma_peak": tflops / PEAK_FP16_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": "pasa_fwd", "achieved": kern_tflops, "peak": PEAK_FP16_TFLOPS,
                      "unit": "TFLOP/s", "frac": kern_tflops / PEAK_FP16_TFLOPS, "traffic": read_traffic(),
-                     "kernel_ms": kern_ms, "flops_per_launch": w.flops},
+                     "kernel_ms": kern_ms, "kernel_ms_median": float(np.median(kern_all)),
+                     "kernel_ms_min": float(kern_all.min()), "flops_per_launch": w.flops},
+        "device": {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
+                   "peak_used": "2500 TFLOP/s dense fp16 MFMA (256 CUs x 4 SIMDs x 1024 FLOP/clk x 2.4 GHz)"},
     }
 
     if not args.no_accuracy:
