@@ -89,6 +89,11 @@ def main():
                     help="before the warmup steps, run untimed steps for this long: an idle GPU takes some hundred "
                          "steps of this size to reach its sustained clock, and steps timed before that run 9 %% slower")
     ap.add_argument("--variant", default="mixed", choices=["mixed", "strict16", "s16", "naive16", "direct"])
+    ap.add_argument("--inputs", default="workload", choices=["workload", "zeros", "ones"],
+                    help="diagnostic: all-zero or all-one q, k, v of the same shape instead of the workload's values.  "
+                         "The instruction stream is the same, the data toggles nothing, and the power management leaves "
+                         "the shader clock high: the difference from the default run is clock, not cycles "
+                         "(no accuracy check and no CPU baseline in that case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -117,6 +122,10 @@ def main():
     tq = torch.from_numpy(np.stack(q_heads)[None]).to(dev)
     tk = torch.from_numpy(np.stack([kv[0] for kv in kv_heads])[None]).to(dev)
     tv = torch.from_numpy(np.stack([kv[1] for kv in kv_heads])[None]).to(dev)
+    if args.inputs != "workload":
+        fill = 0.0 if args.inputs == "zeros" else 1.0
+        tq, tk, tv = (torch.full_like(t, fill) for t in (tq, tk, tv))
+        args.no_accuracy = args.no_cpu_baseline = True
     to = torch.full_like(tq, float("nan"))
     wsb = P.pasa_attn_fwd_workspace(w.B, w.Hq, w.Hkv, w.N, w.d)
     ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
@@ -175,7 +184,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f16",
-        "data": "synthetic",
+        "data": "synthetic" if args.inputs == "workload" else "synthetic, all " + args.inputs + " (clock diagnostic, not the workload's values)",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "d": w.d, "causal": w.causal,
                    "variant": args.variant, "beta": "63.5/64.5", "shift_tile": 128,
                    "mfma_accumulate": "fp32 (hardware); fp16 roundings applied where Algorithm 1 marks them"},
