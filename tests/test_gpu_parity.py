@@ -590,6 +590,31 @@ def test_score_level_staircase(step, causal, variant):
         assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
 
 
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16])
+@pytest.mark.parametrize("step", [3.0, 12.0])
+def test_score_level_staircase_in_unaligned_chunks(step, variant):
+    """The same rising levels reached through query chunks that are not aligned to a wave's 32 rows (some rows of a
+    wave see nothing of a tile while others re-reference their stored output on it), and in bf16."""
+    rng = np.random.default_rng(777)
+    d, N, T = 128, 700, 128
+    u = np.zeros(d)
+    u[9] = 1.0
+    qf = rng.standard_normal((1, 2, N, d)) + 5.0 * u
+    kf = rng.standard_normal((1, 2, N, d)) + (2.0 * step * (np.arange(N) // T))[None, None, :, None] * u
+    q, k = qf.astype(np.float16), kf.astype(np.float16)
+    v = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    ref = po.pasa_bhnd(q, k, v, scale, True, BETA, 128, ORACLE_POLICY[variant])
+    o = gpu_attn_chunks(q, k, v, True, scale, [(0, 77, 0), (77, 300, 77), (377, 323, 377)], variant=variant)
+    c = compare(o, ref)
+    print(VARIANT_NAME[variant], step, c)
+    assert np.isfinite(o).all()
+    assert c["maxabs"] <= 2e-3
+    # one call over all rows gives the same values as the chunks: the per-row state does not depend on the chunking
+    o1, _ = gpu_attn(q, k, v, True, scale, variant)
+    assert np.array_equal(o1, o)
+
+
 # ------------------------------------------------------------------ adaptive start
 
 def _adaptive(q, k, v, causal, scale, variant=P.MIXED):
