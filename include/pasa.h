@@ -95,7 +95,8 @@ int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
 
 /* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes: shifted keys K' and re-tiled values, both fp16
  * (4*B*Hkv*ceil(N/128)*128*d bytes), then one fp16 shift vector per key tile (2*B*Hkv*ceil(N/128)*d bytes, rounded up
- * to a multiple of 256; written and read by PASA_DIRECT only).  Returns 0 if the sizes are invalid. */
+ * to a multiple of 256; written and read by PASA_DIRECT only), then one 64-bit counter per (batch, KV head) (8*B*Hkv
+ * bytes, rounded up to a multiple of 256; used by pasa_attn_fwd_adaptive only).  Returns 0 if the sizes are invalid. */
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
@@ -129,13 +130,15 @@ int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, 
                         float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
 
 /* An adaptive start of PASA (the paper's closing section names it as future work and gives no mechanism; this is
- * the simplest one).  Pass 1 runs the partially low-precision FlashAttention without any shift (PASA_NAIVE16: raw
- * scores rounded to fp16, section 2.1) into o and counts in *opts->overflow_s the raw scores that left the fp16
- * range.  Pass 2 runs opts->variant (not PASA_NAIVE16) into o, but each of its workgroups returns at once unless
- * that counter is non-zero -- decided on the device, no host synchronisation.  So o holds the unshifted result when
- * nothing overflowed anywhere in the call, and the PASA result otherwise.  opts and opts->overflow_s (a DEVICE
- * counter the caller has zeroed; it is the trigger and reports the count) are required, opts->nonfinite_o must be
- * NULL.  Otherwise the rules of pasa_attn_fwd_ex. */
+ * a simple one).  Pass 1 runs the partially low-precision FlashAttention without any shift (PASA_NAIVE16: raw
+ * scores rounded to fp16, section 2.1) into o and counts the raw scores that left the fp16 range: in total in
+ * *opts->overflow_s, and per (batch, KV head) in counters of its own inside the workspace.  Pass 2 runs
+ * opts->variant (not PASA_NAIVE16) into o, but the workgroups of a (batch, KV head) whose counter is zero return at
+ * once -- decided on the device, no host synchronisation.  So the query heads of a (batch, KV head) in which nothing
+ * overflowed keep the unshifted result, and those of a (batch, KV head) in which some raw score of some query head
+ * overflowed get the PASA result (the shifted keys are shared by the query heads of a KV head, so that is the
+ * finest unit).  opts and opts->overflow_s (a DEVICE counter the caller has zeroed; it reports the total) are
+ * required, opts->nonfinite_o must be NULL.  Otherwise the rules of pasa_attn_fwd_ex. */
 int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o,
                            int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                            const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);

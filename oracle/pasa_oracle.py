@@ -453,23 +453,30 @@ def fa_bhnd(q, k, v, scale, causal, T=128, policy=PARTIAL16) -> np.ndarray:
     return out
 
 
-def adaptive_bhnd(q, k, v, scale, causal, beta, T=128, policy=MIXED):
-    """The adaptive start the paper leaves to future work (its closing section), in the simplest form: run the
-    partially low-precision FlashAttention (raw scores stored in fp16, Fig. 2) and keep its result unless some raw
-    score anywhere in the call left the fp16 range; only then run PASA.  Returns (output, triggered)."""
+def adaptive_bhnd(q, k, v, scale, causal, beta, T=128, policy=MIXED, info=None):
+    """The adaptive start the paper leaves to future work (its closing section), in a simple form: run the
+    partially low-precision FlashAttention (raw scores stored in fp16, Fig. 2) and keep its result for the query heads
+    of a (batch, KV head) unless some raw score of one of them left the fp16 range; only those get PASA (they share
+    the shifted keys, so a KV head is the finest unit).  Returns (output, triggered anywhere); info, if a dict,
+    receives 'groups': the boolean [B, Hkv] array of the (batch, KV head)s that switched."""
     B, Hq, N, d = q.shape
     Hkv = k.shape[1]
     out = np.empty((B, Hq, N, d), np.float16)
-    overflowed = 0
+    overflowed = np.zeros((B, Hkv), np.int64)
     for b in range(B):
         for h in range(Hq):
             hk = kv_head(h, Hq, Hkv)
-            info = {}
-            out[b, h] = fa_rows(q[b, h], k[b, hk], v[b, hk], scale, causal, T, PARTIAL16, 0, info)
-            overflowed += info["s_nonfinite"]
-    if overflowed == 0:
-        return out, False
-    return pasa_bhnd(q, k, v, scale, causal, beta, T, policy), True
+            one = {}
+            out[b, h] = fa_rows(q[b, h], k[b, hk], v[b, hk], scale, causal, T, PARTIAL16, 0, one)
+            overflowed[b, hk] += one["s_nonfinite"]
+    for b in range(B):
+        for h in range(Hq):
+            hk = kv_head(h, Hq, Hkv)
+            if overflowed[b, hk]:
+                out[b, h] = pasa_rows(q[b, h], k[b, hk], v[b, hk], scale, causal, beta, T, policy)
+    if info is not None:
+        info["groups"] = overflowed > 0
+    return out, bool(overflowed.any())
 
 
 def rmse(o, o_gold) -> float:

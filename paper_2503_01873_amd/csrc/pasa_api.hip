@@ -91,7 +91,8 @@ double pasa_optimal_beta(double beta0, int n, int tp)
 
 namespace {
 
-// Workspace layout: the K'/V tiles, then (used by PASA_DIRECT only) one fp16 shift vector of d halfs per tile.
+// Workspace layout: the K'/V tiles, then (used by PASA_DIRECT only) one fp16 shift vector of d halfs per tile, then
+// (used by the adaptive entry point only) one 64-bit overflow counter per (batch, KV head).
 size_t tiles_bytes(int B, int Hkv, int N, int d)
 {
     const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
@@ -105,6 +106,11 @@ size_t k0_bytes(int B, int Hkv, int N, int d)
     return (raw + 255) / 256 * 256;
 }
 
+size_t group_counter_bytes(int B, int Hkv)
+{
+    return ((size_t)8 * (size_t)B * (size_t)Hkv + 255) / 256 * 256;
+}
+
 }  // namespace
 
 extern "C" {
@@ -112,7 +118,7 @@ extern "C" {
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
 {
     if (check_shape(B, Hq, Hkv, N, d) != PASA_OK) return 0;
-    return tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d);
+    return tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d) + group_counter_bytes(B, Hkv);
 }
 
 }  // extern "C"
@@ -274,7 +280,7 @@ namespace {
 
 int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
                    float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream,
-                   const unsigned long long* gate)
+                   unsigned long long* overflow_group, const unsigned long long* gate)
 {
     if (q == nullptr || o == nullptr || !aligned(q, 16) || !aligned(o, 16) || o == q) return PASA_EINVAL;
     if (causal != 0 && causal != 1) return PASA_EINVAL;
@@ -301,6 +307,7 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     p.scale = scale;
     p.overflow_s = pr.overflow_s;
     p.nonfinite_o = pr.nonfinite_o;
+    p.overflow_group = overflow_group;
     p.gate = gate;
     p.stream = static_cast<hipStream_t>(stream);
     return pasa_launch_fwd(p) == hipSuccess ? PASA_OK : PASA_ELAUNCH;
@@ -314,7 +321,7 @@ int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, 
                         float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
 {
     return fwd_chunk_impl(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, opts, workspace, workspace_bytes, stream,
-                          nullptr);
+                          nullptr, nullptr);
 }
 
 int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N, int d,
@@ -336,22 +343,29 @@ int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o,
     if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
     st = check_workspace(workspace, workspace_bytes, pasa_attn_fwd_workspace(B, Hq, Hkv, N, d));
     if (st != PASA_OK) return st;
-    // pass 1: no shift, raw scores rounded to fp16, counting those that leave the fp16 range
+    // the per-(batch, KV head) counters live behind the tiles and the shift vectors; cleared by a small kernel
+    unsigned long long* group_cnt = reinterpret_cast<unsigned long long*>(
+        static_cast<char*>(workspace) + tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d));
+    if (pasa_launch_zero(group_cnt, B * Hkv, static_cast<hipStream_t>(stream)) != hipSuccess) return PASA_ELAUNCH;
+    // pass 1: no shift, raw scores rounded to fp16, counting those that leave the fp16 range -- in total (the
+    // caller's counter) and per (batch, KV head)
     pasa_opts first = *opts;
     first.variant = PASA_NAIVE16;
     first.shift_mode = PASA_SHIFT_MEAN;
     first.beta = -1.f;
     st = prepare_kv_impl(k, v, B, Hkv, N, d, scale, &first, workspace, workspace_bytes, stream, nullptr);
     if (st != PASA_OK) return st;
-    st = fwd_chunk_impl(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, &first, workspace, workspace_bytes, stream, nullptr);
+    st = fwd_chunk_impl(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, &first, workspace, workspace_bytes, stream,
+                        group_cnt, nullptr);
     if (st != PASA_OK) return st;
-    // pass 2: the caller's variant, every workgroup leaving at once unless the counter is non-zero
+    // pass 2: the caller's variant; the workgroups of a (batch, KV head) whose counter is zero leave at once, so its
+    // query heads keep the result of pass 1
     pasa_opts second = *opts;
     second.overflow_s = nullptr;
-    st = prepare_kv_impl(k, v, B, Hkv, N, d, scale, &second, workspace, workspace_bytes, stream, opts->overflow_s);
+    st = prepare_kv_impl(k, v, B, Hkv, N, d, scale, &second, workspace, workspace_bytes, stream, group_cnt);
     if (st != PASA_OK) return st;
     return fwd_chunk_impl(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, &second, workspace, workspace_bytes, stream,
-                          opts->overflow_s);
+                          nullptr, group_cnt);
 }
 
 int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N, int d,

@@ -23,14 +23,16 @@ struct PasaLaunch {
     float scale;      // only used by PASA_K_NAIVE16 (static scaling after the first GEMM)
     unsigned long long* overflow_s;
     unsigned long long* nonfinite_o;
-    const unsigned long long* gate;   // non-null: the kernel does nothing unless this device counter is non-zero
+    unsigned long long* overflow_group;   // non-null: the overflow count is also added to entry b * Hkv + hk of this array
+    const unsigned long long* gate;   // non-null: one device counter per (batch, KV head); a workgroup does nothing
+                                      // unless the counter of its own (batch, KV head) is non-zero
     hipStream_t stream;
 };
 
 // Shift + re-tile K (and re-tile V when v != nullptr).  plain_out != nullptr: K' goes there in the
 // plain [B,Hkv,N,d] layout and ws is not written.
 // in_bf16: k and v hold bf16 and are converted to fp16 as they are loaded (outputs stay fp16).
-// gate: non-null: the kernel does nothing unless this device counter is non-zero.
+// gate: non-null: one device counter per (batch, KV head); a head's tiles are left untouched unless its counter is non-zero.
 // PASA_PREP_MEAN:   K' = fp16((K - beta * tile mean) * kscale).
 // PASA_PREP_MATRIX: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
 //                   matrix a I + b (J - I) when beta carries a - b and kscale carries b (N % 128 == 0 only).
@@ -40,5 +42,8 @@ hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_
                             void* k0out, const unsigned long long* gate, hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);
+
+// Sets n 64-bit words to zero with a small kernel (not a memset, so that the call may sit in a captured graph).
+hipError_t pasa_launch_zero(unsigned long long* p, int n, hipStream_t stream);
 
 #endif

@@ -100,7 +100,8 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
                                                     int N, int ntile, double beta, double kscale, int shift_mode,
                                                     int in_bf16, const unsigned long long* gate)
 {
-    if (gate != nullptr && *gate == 0) return;   // adaptive start: nothing overflowed, the shifted pass is not needed
+    // adaptive start: nothing overflowed in this (batch, KV head), its shifted pass is not needed
+    if (gate != nullptr && gate[blockIdx.x / ntile] == 0) return;
 
     // A tile's work is cut into 2*NS blocks (blockIdx.y): NS groups of D/NS channels of K (column means are per
     // channel, so the groups are independent) and NS groups of 128/NS keys of V.  The pass is bound by memory
@@ -340,9 +341,9 @@ __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
               const _Float16* __restrict__ k0, int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale,
               int io_bf16,
-              unsigned long long* ovf_s, unsigned long long* nonfinite_o, const unsigned long long* gate)
+              unsigned long long* ovf_s, unsigned long long* nonfinite_o, unsigned long long* ovf_group,
+              const unsigned long long* gate)
 {
-    if (gate != nullptr && *gate == 0) return;   // adaptive start: nothing overflowed, the shifted pass is not needed
 
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
     constexpr int CB = D / 32;   // 32-channel row blocks of O^T
@@ -388,6 +389,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         grp_id = (wg % nbh) / G;
         hin = (wg % nbh) % G;
     }
+    // adaptive start: nothing overflowed in this (batch, KV head), its shifted pass is not needed (whole workgroup leaves)
+    if (gate != nullptr && gate[grp_id] == 0) return;
     const int b = grp_id / Hkv, hk_ = grp_id % Hkv;
     const int hq = hk_ * G + hin;
     const int hk = hk_;
@@ -943,6 +946,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     }
     if (INSTR) {
         if (ovf_s != nullptr && n_ovf) atomicAdd(ovf_s, n_ovf);
+        if (ovf_group != nullptr && n_ovf) atomicAdd(ovf_group + grp_id, n_ovf);
         if (nonfinite_o != nullptr && n_bad) atomicAdd(nonfinite_o, n_bad);
     }
 }
@@ -960,7 +964,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
                        (_Float16*)p.o, (const _Float16*)p.k0, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
-                       p.nonfinite_o, p.gate);
+                       p.nonfinite_o, p.overflow_group, p.gate);
     return hipGetLastError();
 }
 
@@ -999,6 +1003,19 @@ hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
                            (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
+    return hipGetLastError();
+}
+
+namespace {
+__global__ void pasa_zero_u64(unsigned long long* p, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0ull;
+}
+}  // namespace
+
+hipError_t pasa_launch_zero(unsigned long long* p, int n, hipStream_t stream)
+{
+    hipLaunchKernelGGL(pasa_zero_u64, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
     return hipGetLastError();
 }
 

@@ -65,11 +65,11 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
 
 def test_workspace_size():
     # K'/V tiles, then one fp16 shift vector per key tile (rounded up to 256 bytes)
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256
     assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 96) == 0
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128   # ragged last tile is padded
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64 + 512
-    assert P.pasa_attn_fwd_workspace(1, 1, 1, 128, 64) == 4 * 128 * 64 + 256
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256   # ragged last tile is padded
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64 + 512 + 256
+    assert P.pasa_attn_fwd_workspace(1, 1, 1, 128, 64) == 4 * 128 * 64 + 256 + 256
     assert P.pasa_attn_fwd_workspace(1, 28, 5, 8192, 128) == 0
 
 

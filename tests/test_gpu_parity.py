@@ -664,19 +664,30 @@ def test_adaptive_start_switches_to_pasa_on_overflow(variant):
         assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
 
 
-def test_adaptive_start_one_overflowing_head_is_enough():
+def test_adaptive_start_switches_only_the_kv_head_that_overflowed():
+    # 2 batches x 2 KV heads x 2 query heads each; raw scores overflow in one query head of (batch 1, KV head 0) only
     rng = np.random.default_rng(56)
     N, d = 384, 128
-    q = rng.standard_normal((1, 2, N, d)).astype(np.float16)
-    k = rng.standard_normal((1, 2, N, d)).astype(np.float16)
-    v = rng.standard_normal((1, 2, N, d)).astype(np.float16)
-    q[0, 1] = 30.0
-    k[0, 1] = 30.0
+    q = rng.standard_normal((2, 4, N, d)).astype(np.float16)
+    k = rng.standard_normal((2, 2, N, d)).astype(np.float16)
+    v = rng.standard_normal((2, 2, N, d)).astype(np.float16)
+    q[1, 1] = 30.0
+    k[1, 0] = (30.0 + rng.standard_normal((N, d))).astype(np.float16)
     scale = f32(d ** -0.5)
-    o, count = _adaptive(q, k, v, False, scale)
-    ref, trig = po.adaptive_bhnd(q, k, v, scale, False, BETA)
-    assert trig and count == N * N            # every raw score of head 1 is 128 * 900
+    o, count = _adaptive(q, k, v, True, scale)
+    info = {}
+    ref, trig = po.adaptive_bhnd(q, k, v, scale, True, BETA, info=info)
+    assert trig and info["groups"].tolist() == [[False, False], [True, False]]
+    assert count == N * (N + 1) // 2 + (N // 128) * (128 * 127 // 2)   # head (1, 1): its visible scores, and the masked ones of the diagonal tiles
     assert np.isfinite(o).all() and compare(o, ref)["maxabs"] <= 2e-3
+    plain, _ = gpu_attn(q, k, v, True, scale, P.NAIVE16)
+    shifted, _ = gpu_attn(q, k, v, True, scale, P.MIXED)
+    for b in range(2):
+        for h in range(4):
+            want = shifted if (b, h // 2) == (1, 0) else plain
+            assert np.array_equal(o[b, h].view(np.uint16), want[b, h].view(np.uint16)), (b, h)
+    # query head (1, 0) did not overflow itself and still switched with its KV head
+    assert not np.array_equal(plain[1, 0].view(np.uint16), shifted[1, 0].view(np.uint16))
 
 
 # ------------------------------------------------------------------ capture into a HIP graph

@@ -560,6 +560,19 @@ def test_adaptive_start_triggers_exactly_when_a_raw_score_leaves_fp16():
     q[0, 1] = 30.0
     k2 = np.concatenate([k, np.full((1, 1, N, d), 30.0, np.float16)], axis=1)
     v2 = np.concatenate([v, v], axis=1)
-    out, trig = po.adaptive_bhnd(q, k2, v2, 0.088, False, po.default_beta())
-    assert trig and np.isfinite(out).all()
-    assert np.array_equal(out, po.pasa_bhnd(q, k2, v2, 0.088, False, po.default_beta(), 128, po.MIXED))
+    info = {}
+    out, trig = po.adaptive_bhnd(q, k2, v2, 0.088, False, po.default_beta(), info=info)
+    assert trig and np.isfinite(out).all() and info["groups"].tolist() == [[False, True]]
+    # the (batch, KV head) that overflowed gets PASA, the other keeps the unshifted result
+    assert np.array_equal(out[0, 1], po.pasa_bhnd(q, k2, v2, 0.088, False, po.default_beta(), 128, po.MIXED)[0, 1])
+    assert np.array_equal(out[0, 0], po.fa_bhnd(q, k2, v2, 0.088, False, 128, po.PARTIAL16)[0, 0])
+    # grouped-query heads share the shifted keys: one overflowing query head switches every head of its KV head
+    q4 = np.concatenate([q[:, :1], q[:, :1], q[:, :1], q[:, 1:]], axis=1)          # heads 0, 1 -> KV 0; heads 2, 3 -> KV 1
+    k2[0, 1] = (30.0 + rng.standard_normal((N, d))).astype(np.float16)             # distinct keys: head 2's two results differ
+    out4, trig4 = po.adaptive_bhnd(q4, k2, v2, 0.088, False, po.default_beta(), info=info)
+    assert trig4 and info["groups"].tolist() == [[False, True]]
+    pasa4 = po.pasa_bhnd(q4, k2, v2, 0.088, False, po.default_beta(), 128, po.MIXED)
+    fa4 = po.fa_bhnd(q4, k2, v2, 0.088, False, 128, po.PARTIAL16)
+    assert np.isfinite(fa4[0, 2]).all() and not np.isfinite(fa4[0, 3]).all()       # only head 3 overflows
+    assert np.array_equal(out4[0, 2:], pasa4[0, 2:]) and np.array_equal(out4[0, :2], fa4[0, :2])
+    assert not np.array_equal(pasa4[0, 2], fa4[0, 2])        # head 2 itself did not overflow, yet it switched
