@@ -521,8 +521,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     // Barrier b ends slot b-1 and starts slot b.  Group A runs M(j) in slot 2j and V(j) in slot 2j+1; group B runs
     // M(j) in slot 2j+1 and V(j) in slot 2j+2.  Every wave issues its share of the copies K'(j+1), V(j) from its
-    // vector part V(j) for group A (slot 2j+1) and V(j-1) for group B (slot 2j) -- the matrix part is the critical one
-    // and stays free of them -- and drains them before the barrier that starts slot 2j+2, when group A reads them.
+    // vector part V(j) for group A (slot 2j+1) and V(j-1) for group B (slot 2j) -- the matrix part keeps its MFMA
+    // chain free of them -- and drains them before the barrier that starts slot 2j+2, when group A reads them.
     drain_copies();
     __syncthreads();                       // barrier 0: K'(0) is in LDS
     if (grp == 1) {
@@ -537,8 +537,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // DIRECT and NAIVE16 apply the output rescale behind the MFMAs of the pending product.  Of the row statistics of
     // S' only the maxima of the first three key blocks are taken behind the first GEMM's MFMAs (MIXED, DIRECT; not on
     // tiles that need the mask): the exponentials wait for the maximum, so this shortens the vector part's critical
-    // path (1.8 %).  The row sums stay in the vector part: hooked as well they made the matrix part, which is the
-    // longer part of a slot, longer still (3 % slower).
+    // path (1.8 %).  The row sums stay in the vector part: hooked as well they change nothing (the two wavefronts of
+    // a SIMD share one issue port; what counts is the number of vector instructions, not which of them issues them).
     constexpr bool EARLY_MAX = (VAR == PASA_K_MIXED || DIRECT) && !INSTR;
     float epm[3] = {0.f, 0.f, 0.f};  // maxima of key blocks 0-2 of S'(j), handed from the matrix to the vector part
     bool max_ready = false;
@@ -639,7 +639,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         if (do_g1) {
             if (STRICT) {
                 // the fp16 combination of the product just finished is left to the vector part: hooked behind these
-                // MFMAs it made the matrix part, the longer part of a slot, longer
+                // MFMAs (branch-free, as a hook must be) it was slower
                 gemm1(j, no_hook);
             } else if (EARLY_MAX && !diag && !tail) {
                 gemm1(j, [&](int n) {      // the maximum of a finished 32-key block behind the MFMAs of the next one
