@@ -312,8 +312,8 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 // vector part, so the MFMA pipe and the VALU of a SIMD are busy at the same time.
 //
 //   group A:  M(0) V(0) M(1) V(1) ...        group B:  -  M(0) V(0) M(1) ...
-//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]   with, behind the MFMAs of the same wave, the rescale of
-//          the running output (fp32 variants) or the fp16 combination of the finished product (STRICT16)
+//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]   with, behind the MFMAs of the same wave, the maxima of
+//          the key blocks of S' that are finished (MIXED, DIRECT)
 //   V(j) = [ row statistics, global recovering scalars, exponentials -> P(j), row sum ]
 //
 // LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued from the vector parts,
@@ -321,21 +321,18 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 //
 // Output accumulation.  STRICT16 keeps Algorithm 1's form: the tile product is rounded to fp16 and combined as
 // O = fp16(e^{dm_j} * PV) + fp16(e^{dm_{j-1}} * O).  The fp32 variants accumulate the second GEMM directly onto the
-// running output, which is stored at a scale of its own: O_j = e^{Lc_j} * Ostore_j.
-//  * MIXED and S16 leave the stored output alone and give the tile's P the factor instead: with dp = dm_{j-1} and
-//    dc = dm_j of Algorithm 1's step 3, Lc_j = Lc_{j-1} + dp and P_j = fp16(exp(S' - m'_j + c_j)), c_j = dc - Lc_j, so
-//    Ostore_j = Ostore_{j-1} + P_j V_j and the running sum l is kept at the same scale (l += rowsum(P_j); the final
-//    quotient needs no factor).  c_j is the tile's level relative to the stored scale, which is the level of an earlier
-//    tile: c_j <= 0 unless the running maximum rises.  Only when c_j > 8 is a row's stored output and sum multiplied
-//    by e^{-c_j} (then Lc_j = dc, c_j = 0), a branch taken on a few tiles at the start of a row at most; so P <= e^8,
-//    far inside fp16, and a tile far below the running maximum underflows to zero by itself.  This removes the 64
-//    multiplications per tile and lane of a per-tile rescale and three exponentials from the recovering scalars
-//    (3.7 % of the kernel time); the price is that P is Algorithm 1's exp(S' - m') times e^{c_j} rounded once, not
-//    exp(S' - m') rounded and then scaled, so outputs agree with a step-by-step evaluation to rounding, not bit for bit.
-//  * DIRECT and NAIVE16 rescale the stored output on every tile behind the MFMAs of the second GEMM (Lc_j = dc,
-//    Ostore_j = P_j V_j + g_j * Ostore_{j-1}, g_j = e^{dp + Lc_{j-1} - dc}, P_j = fp16(exp(S' - m'_j)) as printed); a
-//    tile whose level lies more than 60 below the running maximum cannot change an fp32 output and is dropped for that
-//    row (P row zeroed), which keeps g_j <= e^60.
+// running output, which is stored at a scale of its own: O_j = e^{Lc_j} * Ostore_j.  The stored output is left alone
+// and the tile's P takes the factor instead: with dp = dm_{j-1} and dc = dm_j of Algorithm 1's step 3,
+// Lc_j = Lc_{j-1} + dp and P_j = fp16(exp(S' - m'_j + c_j)), c_j = dc - Lc_j, so Ostore_j = Ostore_{j-1} + P_j V_j and
+// the running sum l is kept at the same scale (l += rowsum(P_j); the final quotient needs no factor).  c_j is the
+// tile's level relative to the stored scale, which is the level of an earlier tile: c_j <= 0 unless the running
+// maximum rises.  Only when c_j > 8 is a row's stored output and sum multiplied by e^{-c_j} (then Lc_j = dc, c_j = 0),
+// a branch taken on a few tiles at the start of a row at most; so P <= e^8, far inside fp16, and a tile far below the
+// running maximum underflows to zero by itself.  Against a rescale of the stored output on every tile this removes 64
+// multiplications per tile and lane and three exponentials from the recovering scalars (3.7 % of the kernel time);
+// the price is that P is Algorithm 1's exp(S' - m') times e^{c_j} rounded once, not exp(S' - m') rounded and then
+// scaled, so outputs agree with a step-by-step evaluation to rounding, not bit for bit.  DIRECT (levels m' + c) and
+// NAIVE16 (plain online softmax: P relative to the running maximum, dc = 0) use the same bookkeeping.
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
@@ -531,11 +528,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     }
 
     // Hand-offs between the parts of one wave.
-    float g_pend = 1.f;              // DIRECT, NAIVE16: factor for the stored output before the pending product is added
-    constexpr bool LAZY = (VAR == PASA_K_MIXED || VAR == PASA_K_S16);   // the factor goes to P, not to the stored output
+    constexpr bool LAZY = !STRICT;   // fp32 variants: the recovering factor goes to P, not to the stored output
     constexpr float CMAX = 8.f;      // LAZY: P may exceed 1 by at most e^CMAX before the row re-references its scale
-    // DIRECT and NAIVE16 apply the output rescale behind the MFMAs of the pending product.  Of the row statistics of
-    // S' only the maxima of the first three key blocks are taken behind the first GEMM's MFMAs (MIXED, DIRECT; not on
+    // Of the row statistics of S' only the maxima of the first three key blocks are taken behind the first GEMM's MFMAs (MIXED, DIRECT; not on
     // tiles that need the mask): the exponentials wait for the maximum, so this shortens the vector part's critical
     // path (1.8 %).  The row sums stay in the vector part: hooked as well they change nothing (the two wavefronts of
     // a SIMD share one issue port; what counts is the number of vector instructions, not which of them issues them).
@@ -548,8 +543,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // fragments PF instructions ahead.  hook(n) is vector work of the same wave placed behind MFMA n; it is issued
     // while that MFMA executes.
     // The code generator otherwise sinks a hook's arithmetic into the later block that uses its result, away from the
-    // MFMA it was meant to run behind; an empty volatile asm that takes and returns the values keeps it in place.
-#define PASA_PIN2(a, b) asm volatile("" : "+v"(a), "+v"(b))
+    // MFMA it was meant to run behind; an empty volatile asm that takes and returns the value keeps it in place.
 #ifndef PASA_PF
 #define PASA_PF 3
 #endif
@@ -618,22 +612,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         __builtin_amdgcn_s_setprio(1);
         // ---- pending product of tile j-1 ----
         if (do_g2) {
-            if (STRICT || LAZY) {
-                gemm2(j - 1, no_hook);
-            } else {
-                // the stored output takes its factor block by block, one block ahead of the MFMA chain that adds to it
-#pragma unroll
-                for (int i = 0; i < 16; ++i) O[0][i] *= g_pend;
-                gemm2(j - 1, [&](int n) {
-                    const int cb = n / 8, kk = n % 8;
-                    if (cb + 1 < CB) {
-                        float x0 = O[cb + 1][2 * kk] * g_pend, x1 = O[cb + 1][2 * kk + 1] * g_pend;
-                        PASA_PIN2(x0, x1);
-                        O[cb + 1][2 * kk] = x0;
-                        O[cb + 1][2 * kk + 1] = x1;
-                    }
-                });
-            }
+            gemm2(j - 1, no_hook);
         }
         // ---- S'(j) ----
         if (do_g1) {
@@ -649,7 +628,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                     float macc = ks ? epm[kb] : -__builtin_inff();
 #pragma unroll
                     for (int i = ks * PER; i < (ks + 1) * PER; ++i) macc = __builtin_fmaxf(macc, S[kb][i]);
-                    asm volatile("" : "+v"(macc));    // stays behind this MFMA (see PASA_PIN2)
+                    asm volatile("" : "+v"(macc));    // stays behind this MFMA (see above)
                     epm[kb] = macc;
                 });
                 max_ready = true;
@@ -759,22 +738,26 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             // first rows see none of it: those rows keep their state and add nothing.
             const bool unseen = CAUSAL && diag && (row0 + row < j * T);
             // ---- reference level for exp: local m' (PASA), running max (plain FlashAttention) ----
-            float mref = unseen ? 0.f : mx, e_old = 0.f;
+            float mref = unseen ? 0.f : mx;
+            float c_adj = 0.f;    // LAZY: log of the factor this tile's P carries (its level relative to the stored scale)
+            bool resc = false;    // LAZY: this row re-references its stored output and sum to the level of tile j
+            float lc_resc = 0.f;  // LAZY: log of the factor that does it
             if (NAIVE) {
+                // plain online softmax (Eq. (4)-(8)) on the running maximum, the stored output handled as in MIXED:
+                // its log scale moves by m_{j-1} - m_j, P carries the factor, no per-tile rescale
                 const float mnew = __builtin_fmaxf(m, mx);
-                e_old = exp_nat(m - mnew);
+                const bool keep = first || unseen;
+                const float lcn = Lc + (m - mnew), c = -lcn;
+                resc = !keep && c > CMAX;
+                lc_resc = lcn;
+                c_adj = (keep || resc) ? 0.f : c;
+                Lc = first ? 0.f : unseen ? Lc : resc ? 0.f : lcn;
                 m = mnew;
                 mref = mnew;
             }
             // ---- fp32 variants: global recovering (step 3) and the factor of the output or of P now, before the
             // exponentials.  Only the running sum needs l'; the rest is a chain of dependent scalar operations whose
             // latency is hidden when the exponentials that follow can issue in between. ----
-            float g = 1.f;        // DIRECT, NAIVE16: factor for the stored output before tile j is accumulated
-            bool drop = false;    // DIRECT: this row's tile j is too far below the running maximum to matter
-            float l_ep = 0.f, l_ec = 1.f;   // DIRECT: l <- l_ep * l + l_ec * l'  (first tile: l = l')
-            float c_adj = 0.f;    // LAZY: log of the factor this tile's P carries (its level relative to the stored scale)
-            bool resc = false;    // LAZY: this row re-references its stored output and sum to the level of tile j
-            float lc_resc = 0.f;  // LAZY: log of the factor that does it
             bool l_keep = false;             // STRICT16: this row's state is not touched by this tile
             if (STRICT) {
                 // Step 3 with every operation rounded to fp16, in the order Algorithm 1 states them; computed before
@@ -804,12 +787,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 const float dp = m - mn;
                 const float dc = lev - mn;
                 const bool keep = first || unseen;
-                drop = !keep && dc < -60.f;
-                const float g_all = exp_nat((dp + Lc) - dc);
-                g = (keep || drop) ? 1.f : g_all;
-                Lc = first ? 0.f : unseen ? Lc : drop ? dp + Lc : dc;
-                l_ep = first ? 0.f : unseen ? 1.f : exp_nat(dp);
-                l_ec = unseen ? 0.f : first ? 1.f : exp_nat(dc);
+                const float lcn = Lc + dp, c = dc - lcn;
+                resc = !keep && c > CMAX;
+                lc_resc = -c;
+                c_adj = (keep || resc) ? 0.f : c;
+                Lc = first ? 0.f : unseen ? Lc : resc ? dc : lcn;
                 m = first ? lev : unseen ? m : mn;
             } else if (!STRICT && !NAIVE) {
                 // Written without branches (the first tile and rows that see nothing of the tile select their values at
@@ -882,28 +864,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
 
             // ---- the running sum (step 4); STRICT16: the whole of step 3 and 4 in fp16 ----
-            if (NAIVE) {
-                l = e_old * l + lsum;
-                g = e_old;
-            } else if (LAZY) {
+            if (LAZY) {
                 l += lsum;                     // the sum is kept at the stored output's scale (first tile: l was 0)
-            } else if (!STRICT) {
-                l = first ? lsum : l_ep * l + l_ec * lsum;
             } else {
                 // fp16, each operation rounded: l = fp16(fp16(e^{dm_{j-1}} l) + fp16(e^{dm_j} l')); first tile: l = l'
                 const _Float16 lo = (_Float16)l, ln = (_Float16)lsum;
                 const float ln_all = (float)(_Float16)((_Float16)((_Float16)ep_s * lo) + (_Float16)((_Float16)ec_s * ln));
                 l = first ? lsum : l_keep ? l : ln_all;
-            }
-            if (!STRICT && !LAZY) {
-                if (__builtin_amdgcn_ballot_w64(drop) != 0ull) {
-                    // rare; the empty asm keeps the compiler from turning this branch into 32 selects on every tile
-                    asm volatile("" ::: "memory");
-#pragma unroll
-                    for (int kk = 0; kk < 8; ++kk)
-                        if (drop) Pf[kk] = (h8)(_Float16)0;
-                }
-                g_pend = first ? 1.f : g;     // applied under the next first GEMM, before this tile's product is added
             }
         }
         if (grp == 0) drain_copies();
@@ -915,7 +882,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     unsigned long long n_bad = 0;
     if (wave_valid) {
         if (STRICT) fold16(J_w - 1);
-        const float oscale = STRICT ? 0.f : LAZY ? 1.0f / l : exp_nat(Lc) / l;
+        const float oscale = STRICT ? 0.f : 1.0f / l;
         _Float16* obase = o + ((size_t)(b * Hq + hq) * Nq) * D;
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
