@@ -398,6 +398,27 @@ def test_table4_partial_overflow_rows_are_partial(golden):
     assert 0.0 < frac[15.0] < frac[20.0] < 0.5
 
 
+def test_overflow_onset_of_the_uniform_generator():
+    """Section 3.3.1: with x0 = 20 the partially low-precision attention starts to overflow once the amplitude passes
+    about 10.  From the generator alone: a raw score is a sum of 128 products of independent U(20 - Am, 20 + Am)
+    values, mean 128 * 400 = 51200, standard deviation sqrt(128 * ((400 + Am^2 / 3)^2 - 400^2)); 65504 lies 15 standard
+    deviations away at Am = 5 (no score of the 1.6 million overflows) and 3.4 away at Am = 20 (about 0.03 % do)."""
+    scale = 1 / math.sqrt(128)
+    for am, lo, hi in ((5.0, 0.0, 0.0), (20.0, 1e-4, 2e-3)):
+        sd = math.sqrt(128 * ((400 + am * am / 3) ** 2 - 400 ** 2))
+        z = (65504 - 51200) / sd
+        q, k, v = gen_uniform_benchmark(20.0, am, seed=11, shape=(1, 1, 1280, 128))
+        info = {}
+        po.fa_rows(q[0, 0], k[0, 0], v[0, 0], scale, False, 128, po.PARTIAL16, info=info)
+        frac = info["s_nonfinite"] / info["s_seen"]
+        assert lo <= frac <= hi, (am, z, frac)
+        tail = 0.5 * math.erfc(z / math.sqrt(2))           # normal approximation of the sum of 128 products
+        assert frac <= 4 * tail + 1e-12 and (am == 5.0 or frac >= tail / 4)
+        info = {}
+        po.pasa_rows(q[0, 0], k[0, 0], v[0, 0], scale, False, po.default_beta(), 128, po.STRICT16, info=info)
+        assert info["s_nonfinite"] == 0
+
+
 def test_overflow_workload_naive_overflows_pasa_does_not():
     w = workload("overflow_bias").with_n(512)
     q = gen_q_head(w, 0, 0)
