@@ -402,7 +402,7 @@ def test_overflow_onset_of_the_uniform_generator():
     """Section 3.3.1: with x0 = 20 the partially low-precision attention starts to overflow once the amplitude passes
     about 10.  From the generator alone: a raw score is a sum of 128 products of independent U(20 - Am, 20 + Am)
     values, mean 128 * 400 = 51200, standard deviation sqrt(128 * ((400 + Am^2 / 3)^2 - 400^2)); 65504 lies 15 standard
-    deviations away at Am = 5 (no score of the 1.6 million overflows) and 3.4 away at Am = 20 (about 0.03 % do)."""
+    deviations away at Am = 5 (no score of the 1.6 million overflows) and 3.6 away at Am = 20 (0.017 % do; counted: 0.016 %)."""
     scale = 1 / math.sqrt(128)
     for am, lo, hi in ((5.0, 0.0, 0.0), (20.0, 1e-4, 2e-3)):
         sd = math.sqrt(128 * ((400 + am * am / 3) ** 2 - 400 ** 2))
