@@ -618,6 +618,45 @@ def test_score_level_staircase_in_unaligned_chunks(step, variant):
     assert np.array_equal(o1, o)
 
 
+# ------------------------------------------------------------------ exact symmetries (no oracle involved)
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16, P.DIRECT, P.NAIVE16])
+def test_powers_of_two_commute_with_every_rounding_on_the_gpu(variant):
+    """Doubling Q and halving the scale changes no bit of the output; doubling V doubles it exactly (outputs below
+    2^-13 aside, where fp16 is subnormal).  The keys are drawn so that no shifted key is tiny."""
+    rng = np.random.default_rng(404)
+    N, d = 700, 128
+    q = rng.standard_normal((1, 2, N, d)).astype(np.float16)
+    k = (3.0 + rng.choice([-1.0, 1.0], (1, 1, N, d)) * rng.uniform(0.25, 1.0, (1, 1, N, d))).astype(np.float16)
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    scale = f32(2.0 ** -4)
+    base, _ = gpu_attn(q, k, v, True, scale, variant)
+    big = np.abs(base.astype(np.float64)) >= 2.0 ** -13
+    assert np.isfinite(base).all() and big.mean() > 0.99
+    if variant != P.NAIVE16:       # NAIVE16 scales the rounded raw scores in fp32 after the GEMM: not the same roundings
+        q2, _ = gpu_attn((2 * q).astype(np.float16), k, v, True, f32(2.0 ** -5), variant)
+        assert np.array_equal(q2[big], base[big])
+    if variant != P.STRICT16:      # its fp16 output combination meets subnormal products
+        v2, _ = gpu_attn(q, k, (2 * v).astype(np.float16), True, scale, variant)
+        assert np.array_equal(v2.astype(np.float64)[big], 2.0 * base.astype(np.float64)[big])
+
+
+def test_first_two_key_tiles_enter_symmetrically_in_strict16():
+    """Algorithm 1 combines the first two tiles with commutative operations only (F = (Sbar'_1 + Sbar'_2) / 2, the two
+    corrections, the maximum, the two-term sums for l and O), so exchanging them changes no bit -- in the oracle
+    (pinned there) and in the kernel's literal fp16 variant."""
+    rng = np.random.default_rng(405)
+    N, d, T = 384, 64, 128
+    q = rng.standard_normal((1, 2, 100, d)).astype(np.float16)
+    k = (rng.standard_normal((1, 1, N, d)) + 2.0).astype(np.float16)
+    v = rng.standard_normal((1, 1, N, d)).astype(np.float16)
+    swap01 = np.concatenate([np.arange(T, 2 * T), np.arange(0, T), np.arange(2 * T, N)])
+    chunks = [(0, 100, 0)]
+    a = gpu_attn_chunks(q, k, v, False, f32(0.125), chunks, variant=P.STRICT16)
+    b = gpu_attn_chunks(q, k[:, :, swap01], v[:, :, swap01], False, f32(0.125), chunks, variant=P.STRICT16)
+    assert np.isfinite(a).all() and np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
 # ------------------------------------------------------------------ adaptive start
 
 def _adaptive(q, k, v, causal, scale, variant=P.MIXED):

@@ -360,6 +360,64 @@ def test_rmse_closed_form():
     assert po.rmse(g, g) == 0.0
 
 
+# ------------------------------------------------------------------ exact symmetries of the rounded algorithm
+
+@pytest.mark.parametrize("policy", [po.MIXED, po.STRICT16, po.PARTIAL16])
+def test_powers_of_two_commute_with_every_rounding(policy):
+    """Doubling Q and halving the scale leaves K' a power of two smaller and S' unchanged, bit for bit (a factor 2 is
+    exact in every format as long as nothing is subnormal: the keys are drawn so that no K' is tiny, and outputs
+    below 2^-13 are left out); doubling V doubles the output exactly.  A scale applied twice, not at all, or to the
+    wrong operand breaks one of the two."""
+    rng = np.random.default_rng(404)
+    N, d = 300, 64
+    q = rng.standard_normal((N, d)).astype(np.float16)
+    k = (3.0 + rng.choice([-1.0, 1.0], (N, d)) * rng.uniform(0.25, 1.0, (N, d))).astype(np.float16)
+    v = rng.standard_normal((N, d)).astype(np.float16)
+    beta = po.default_beta()
+    base = po.pasa_rows(q, k, v, 0.125, True, beta, 128, policy)
+    big = np.abs(base.astype(np.float64)) >= 2.0 ** -13
+    assert big.mean() > 0.99
+    q2 = po.pasa_rows((2 * q).astype(np.float16), k, v, 0.0625, True, beta, 128, policy)
+    assert np.array_equal(q2[big], base[big])
+    two_v = po.pasa_rows(q, k, (2 * v).astype(np.float16), 0.125, True, beta, 128, policy)
+    assert np.array_equal(two_v.astype(np.float64)[big], 2.0 * base.astype(np.float64)[big])
+    # and the partially low-precision FlashAttention of Eq. (1)-(8)
+    fa = po.fa_rows(q, k, v, 0.125, True, 128, policy)
+    fa2 = po.fa_rows(q, k, (2 * v).astype(np.float16), 0.125, True, 128, policy)
+    bigf = np.abs(fa.astype(np.float64)) >= 2.0 ** -13
+    assert np.array_equal(fa2.astype(np.float64)[bigf], 2.0 * fa.astype(np.float64)[bigf])
+
+
+def test_order_of_the_keys_inside_a_tile_does_not_matter():
+    """Every sum over the keys of a tile (the tile mean of K, Sbar', l', P V) is an exact accumulation rounded once, and
+    the maximum is order-free: permuting the keys of each 128-key tile (with their values) changes no bit."""
+    rng = np.random.default_rng(405)
+    N, d, T = 384, 64, 128
+    q = rng.standard_normal((40, d)).astype(np.float16)
+    k = (rng.standard_normal((N, d)) + 2.0).astype(np.float16)
+    v = rng.standard_normal((N, d)).astype(np.float16)
+    perm = np.concatenate([t * T + rng.permutation(T) for t in range(N // T)])
+    for policy in (po.MIXED, po.STRICT16):
+        a = po.pasa_rows(q, k, v, 0.125, False, po.default_beta(), T, policy)
+        b = po.pasa_rows(q, k[perm], v[perm], 0.125, False, po.default_beta(), T, policy)
+        assert np.array_equal(a, b)
+    # The first two tiles enter symmetrically -- F = (Sbar'_1 + Sbar'_2) / 2, the two corrections, the maximum and the
+    # two-term sums of l and O are all commutative in floating point -- so exchanging them changes no bit either.  (A
+    # first tile initialised differently from "the state is the tile's own values" would break this.)
+    swap01 = np.concatenate([np.arange(T, 2 * T), np.arange(0, T), np.arange(2 * T, N)])
+    for policy in (po.MIXED, po.STRICT16):
+        a = po.pasa_rows(q, k, v, 0.125, False, po.default_beta(), T, policy)
+        assert np.array_equal(a, po.pasa_rows(q, k[swap01], v[swap01], 0.125, False, po.default_beta(), T, policy))
+    # Beyond that the order of the tiles does matter in low precision (they are combined one after the other) ...
+    swap02 = np.concatenate([np.arange(2 * T, N), np.arange(T, 2 * T), np.arange(0, T)])
+    c = po.pasa_rows(q, k[swap02], v[swap02], 0.125, False, po.default_beta(), T, po.STRICT16)
+    assert (a != c).mean() > 0.1
+    # ... but not in fp64, where the method is the plain definition
+    a64 = po.pasa_rows(q, k, v, 0.125, False, po.default_beta(), T, po.EXACT64)
+    c64 = po.pasa_rows(q, k[swap02], v[swap02], 0.125, False, po.default_beta(), T, po.EXACT64)
+    assert np.allclose(a64, c64, rtol=0, atol=1e-12)
+
+
 # ------------------------------------------------------------------ overflow behaviour the paper reports
 
 @pytest.mark.parametrize("row", [1, 4])
