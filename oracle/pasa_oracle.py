@@ -211,7 +211,8 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
     float32 values (numpy has no bf16 type).
 
     Rows are independent: all state (F, m, l, O) is per query row.  If `info` is a dict it receives
-    max |S'| over finite entries, the number of non-finite S' entries and of S' entries seen.
+    max |S'| over finite entries, the number of non-finite S' entries and of S' entries seen, and the final per-row
+    state F, m, l (copies).
     """
     st, pS, pP, pO = policy.stat, policy.S, policy.P, policy.O
     Q64 = np.asarray(Q).astype(np.float64)
@@ -271,7 +272,7 @@ def pasa_rows(Q, K, V, scale: float, causal: bool, beta: float, T: int = 128,
         else:
             out = (O / l[:, None]).astype(np.float16)
     if info is not None:
-        info.update(smax=smax, s_nonfinite=s_nonfinite, s_seen=s_seen)
+        info.update(smax=smax, s_nonfinite=s_nonfinite, s_seen=s_seen, F=F.copy(), m=m.copy(), l=l.copy())
     return out
 
 

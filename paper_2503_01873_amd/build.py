@@ -48,24 +48,5 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     return out
 
 
-PROBES = ("probe_mfma_sustained", "probe_valu_issue")
-PROBE = os.path.join(PKG, PROBES[0])
-
-
-def build_probe(verbose: bool = False) -> str:
-    """Builds the stand-alone measurement tools (not part of libpasa): the sustained MFMA rate probe and the probe of
-    vector-instruction issue cost beside a wavefront that issues MFMAs.  Returns the path of the first."""
-    for name in PROBES:
-        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", os.path.join(CSRC, name + ".hip"), "-o", os.path.join(PKG, name)]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        res = subprocess.run(cmd, capture_output=True, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))
-    print(build_probe(verbose=True))
