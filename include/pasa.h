@@ -106,6 +106,21 @@ int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
                      int B, int Hq, int Hkv, int N, int d, int causal, float scale,
                      const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): pasa_attn_fwd_ex with its workspace in a fixed array of PASA_STATIC_WORKSPACE_BYTES of
+ * device memory that belongs to the library (one copy per GPU the library is used on, held until the process ends).
+ * Calls no hipMalloc / hipFree and no allocating routine.  PASA_EWORKSPACE if
+ * pasa_attn_fwd_workspace(B, Hq, Hkv, N, d) exceeds PASA_STATIC_WORKSPACE_BYTES (e.g. B*Hkv*N*d > 8 Mi elements
+ * for N % 128 == 0); otherwise arguments, options and errors as pasa_attn_fwd_ex.  The device that is current at
+ * the call must be the stream's.  The first call on a device looks the array's address up (no allocation, but make
+ * it before a capture begins).  All calls on one GPU share the one array: calls that may overlap in time on one GPU
+ * (different streams, or different threads) race on it and must be serialised by the caller; the array keeps the
+ * previous call's contents, none of which a later call reads. */
+#define PASA_STATIC_WORKSPACE_BYTES (33u << 20)
+int pasa_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
+                         int B, int Hq, int Hkv, int N, int d, int causal, float scale,
+                         const pasa_opts* opts, void* stream);
+
 /* The two halves of pasa_attn_fwd_ex as separate calls, for callers that attend to the same keys and
  * values more than once (several query chunks against one K/V): pasa_prepare_kv runs Algorithm 1's
  * pre-processing loop (key shift, Eq. (11)) and re-tiles K' and V into `workspace`;

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
     L.pasa_attn_fwd_workspace.restype = sz
     L.pasa_attn_fwd_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_attn_fwd_ex.restype = ci
+    L.pasa_attn_fwd_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp]
+    L.pasa_attn_fwd_static.restype = ci
     L.pasa_prepare_kv.argtypes = [vp, vp, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_prepare_kv.restype = ci
     L.pasa_attn_fwd_prepared.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
@@ -140,6 +142,19 @@ def pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, workspace, wor
                                 None if opts_null else ctypes.byref(opts), _ptr(workspace), int(workspace_bytes),
                                 _stream(stream))
     return _check(st, "pasa_attn_fwd_ex", check)
+
+
+STATIC_WORKSPACE_BYTES = 33 << 20      # PASA_STATIC_WORKSPACE_BYTES of include/pasa.h
+
+
+def pasa_attn_fwd_static(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, stream=None,
+                         beta=-1.0, variant=MIXED, shift_tile=128, overflow_s=None, nonfinite_o=None,
+                         shift_mode=SHIFT_MEAN, io_dtype=IO_F16, opts_null=False, check=True) -> int:
+    opts = pasa_opts(float(beta), int(variant), int(shift_tile), _ptr(overflow_s), _ptr(nonfinite_o), int(shift_mode),
+                     int(io_dtype))
+    st = lib().pasa_attn_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(o), B, Hq, Hkv, N, d, int(causal), float(scale),
+                                    None if opts_null else ctypes.byref(opts), _stream(stream))
+    return _check(st, "pasa_attn_fwd_static", check)
 
 
 def pasa_prepare_kv(k, v, B, Hkv, N, d, scale, workspace, workspace_bytes, stream=None, beta=-1.0, variant=MIXED,

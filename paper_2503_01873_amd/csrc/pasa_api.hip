@@ -1,8 +1,11 @@
 // libpasa host layer: the C ABI declared in include/pasa.h.
-// Argument validation, the optimal-beta solve (host, fp64) and kernel dispatch.  No device code here.
+// Argument validation, the optimal-beta solve (host, fp64) and kernel dispatch.  No kernels here; the only device
+// object is the fixed workspace of pasa_attn_fwd_static.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+
+#include <mutex>
 
 #include "pasa.h"
 #include "pasa_kernels.h"
@@ -413,3 +416,56 @@ int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o, int B, i
 }
 
 }  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// The entry point that allocates nothing.  Its workspace (shifted keys, re-tiled values, shift vectors) is this
+// fixed array in device memory; every GPU the library is used on holds its own copy at its own address until the
+// process ends.  In host code the array's name only stands for the symbol: the address on the current device comes
+// from hipGetSymbolAddress, once per device, and only that address is handed to the kernels.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PASA_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, filled on the first call there
+
+int static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return PASA_ELAUNCH;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return PASA_ELAUNCH;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PASA_OK;
+}
+
+}  // namespace
+
+extern "C" int pasa_attn_fwd_static(const void* q, const void* k, const void* v, void* o, int B, int Hq, int Hkv, int N,
+                                    int d, int causal, float scale, const pasa_opts* opts, void* stream)
+{
+    const int st = check_shape(B, Hq, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    // sizes beyond the fixed array are refused before anything else is looked at
+    const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
+    if (need == 0 || need > (size_t)PASA_STATIC_WORKSPACE_BYTES) return PASA_EWORKSPACE;
+    void* ws = nullptr;
+    const int sp = static_scratch(&ws);
+    if (sp != PASA_OK) return sp;
+    // every byte of the workspace that the main kernel reads is rewritten by the pre-processing kernel of the same
+    // call (the padding keys of a ragged last tile included), so nothing has to be cleared between calls
+    return pasa_attn_fwd_ex(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, opts, ws, (size_t)PASA_STATIC_WORKSPACE_BYTES,
+                            stream);
+}

@@ -23,13 +23,24 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     L = P.lib()
     names = _declared_functions()
-    assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_workspace", "pasa_prepare_kv",
+    assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_static", "pasa_attn_fwd_workspace", "pasa_prepare_kv",
             "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_attn_fwd_adaptive", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_shift_keys_direct",
             "pasa_optimal_beta", "pasa_invariance_rounded",
             "pasa_status_string", "pasa_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
     assert P.pasa_version() >= 100
+
+
+def test_static_entry_point_checks_sizes_on_the_host():
+    # shape errors and sizes beyond the library's fixed workspace are refused before any device is touched
+    assert P.pasa_attn_fwd_static(16, 16, 16, 32, 1, 3, 2, 256, 64, 0, 0.125, check=False) == 1      # Hq % Hkv
+    assert P.pasa_attn_fwd_static(16, 16, 16, 32, 1, 1, 1, 256, 96, 0, 0.125, check=False) == 2      # d
+    assert P.pasa_attn_fwd_workspace(14, 5, 5, 9216, 64) > P.STATIC_WORKSPACE_BYTES
+    assert P.pasa_attn_fwd_static(16, 16, 16, 32, 14, 5, 5, 9216, 64, 0, 0.125, check=False) == 4
+    assert P.pasa_attn_fwd_workspace(1, 8, 8, 8192, 128) <= P.STATIC_WORKSPACE_BYTES
+    text = open(os.path.join(ROOT, "include", "pasa.h")).read()
+    assert "#define PASA_STATIC_WORKSPACE_BYTES (33u << 20)" in text and P.STATIC_WORKSPACE_BYTES == 33 << 20
 
 
 def test_missing_library_fails_loudly(monkeypatch):
