@@ -312,12 +312,11 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 // vector part, so the MFMA pipe and the VALU of a SIMD are busy at the same time.
 //
 //   group A:  M(0) V(0) M(1) V(1) ...        group B:  -  M(0) V(0) M(1) ...
-//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]   with, behind the MFMAs of the same wave, the maxima of
-//          the key blocks of S' that are finished (MIXED, DIRECT)
+//   M(j) = [ O^T += V(j-1)^T P(j-1)^T ,  S'^T = K'(j) Q^T ]
 //   V(j) = [ row statistics, global recovering scalars, exponentials -> P(j), row sum ]
 //
-// LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued from the vector parts,
-// one to two slots before the first matrix part that reads them.
+// LDS holds two K' tiles and two V tiles; tile copies are direct global->LDS loads issued at the start of the vector
+// parts, one to two slots before the first matrix part that reads them.
 //
 // Output accumulation.  STRICT16 keeps Algorithm 1's form: the tile product is rounded to fp16 and combined as
 // O = fp16(e^{dm_j} * PV) + fp16(e^{dm_{j-1}} * O).  The fp32 variants accumulate the second GEMM directly onto the
@@ -480,8 +479,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     };
 
     // The copies of the even global slot sg are K'(sg/2 + 1) and V(sg/2); each wave owns 2*CPW of their 1 KiB pieces.
-    // They are issued one at a time, spread over the slot, because a burst of 64 wave-wide copies fills the address
-    // FIFO of the texture path and stalls the issuing waves for hundreds of cycles.
+    // A wave issues its eight pieces back to back at the start of its vector part (one wave-wide copy each, sharing M0
+    // through immediate offsets).
     auto issue_piece = [&](int sg, auto piece_c) {
         constexpr int piece = decltype(piece_c)::value;       // 0 .. 2*CPW-1: K' pieces first, then V pieces
         const int jl = sg >> 1;
@@ -530,29 +529,21 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // Hand-offs between the parts of one wave.
     constexpr bool LAZY = !STRICT;   // fp32 variants: the recovering factor goes to P, not to the stored output
     constexpr float CMAX = 8.f;      // LAZY: P may exceed 1 by at most e^CMAX before the row re-references its scale
-    // Of the row statistics of S' only the maxima of the first three key blocks are taken behind the first GEMM's MFMAs (MIXED, DIRECT; not on
-    // tiles that need the mask): the exponentials wait for the maximum, so this shortens the vector part's critical
-    // path (1.8 %).  The row sums stay in the vector part: hooked as well they change nothing (the two wavefronts of
-    // a SIMD share one issue port; what counts is the number of vector instructions, not which of them issues them).
-    constexpr bool EARLY_MAX = (VAR == PASA_K_MIXED || DIRECT) && !INSTR;
-    float epm[3] = {0.f, 0.f, 0.f};  // maxima of key blocks 0-2 of S'(j), handed from the matrix to the vector part
-    bool max_ready = false;
     float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile whose S' was computed last
 
-    // Both GEMMs run as one chain of MFMAs per accumulator block (the block index is the slow one), with the LDS
-    // fragments PF instructions ahead.  hook(n) is vector work of the same wave placed behind MFMA n; it is issued
-    // while that MFMA executes.
-    // The code generator otherwise sinks a hook's arithmetic into the later block that uses its result, away from the
-    // MFMA it was meant to run behind; an empty volatile asm that takes and returns the value keeps it in place.
+    // Both GEMMs run k-step by k-step: the four MFMAs of a k-step share their B operand (the Q or P fragment) and go
+    // to the four accumulator blocks in turn, so consecutive MFMAs never depend on each other and the B registers are
+    // read four times in a row (measured 1.4 % faster than one dependent chain per accumulator block, with the
+    // maxima of finished blocks taken behind the MFMAs of the next).  LDS fragments are fetched PF instructions ahead.
 #ifndef PASA_PF
 #define PASA_PF 3
 #endif
     constexpr int PF = PASA_PF;
     constexpr int NM1 = 4 * KS;      // MFMAs of the first GEMM:  n = kb * KS + ks
     constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM: n = cb * 8 + kk
-    auto gemm1 = [&](int jt, auto&& hook) {   // S'^T of tile jt: 128 keys x 32 queries
+    auto gemm1 = [&](int jt) {   // S'^T of tile jt: 128 keys x 32 queries; MFMA n: key block n % 4, k-step n / 4
         const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (jt & 1) * KT_BYTES);
-        auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_k + ((2 * (n % KS) + lh) * T + 32 * (n / KS) + lq) * 8); };
+        auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_k + ((2 * (n / 4) + lh) * T + 32 * (n % 4) + lq) * 8); };
         h8 a[PF];
 #pragma unroll
         for (int n = 0; n < PF; ++n) a[n] = frag(n);
@@ -570,39 +561,36 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         PASA_FENCE();
 #pragma unroll
         for (int n = 0; n < NM1; ++n) {
-            const int kb = n / KS, ks = n % KS;
-            if (DIRECT && n == KS) cj = scale * sum32(S[3][0]);     // before the last block's chain reuses S[3]
+            const int kb = n % 4, ks = n / 4;
+            if (DIRECT && n == 3) cj = scale * sum32(S[3][0]);      // before the last block's first MFMA reuses S[3]
             if (ks == 0)
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], (f16v)0.f, 0, 0, 0);
             else
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], S[kb], 0, 0, 0);
             PASA_FENCE();
-            hook(n);
             if (n + PF < NM1) a[n % PF] = frag(n + PF);
             PASA_FENCE();
         }
     };
-    auto gemm2 = [&](int jt, auto&& hook) {   // (P V)^T of tile jt: D channels x 32 queries; runs during M(jt+1)
+    auto gemm2 = [&](int jt) {   // (P V)^T of tile jt: D channels x 32 queries; runs during M(jt+1); MFMA n: channel block n % CB, k-step n / CB
         const _Float16* lds_v = reinterpret_cast<const _Float16*>(smem + 2 * KT_BYTES + (jt & 1) * KT_BYTES);
-        auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_v + ((2 * (n % 8) + lh) * D + 32 * (n / 8) + lq) * 8); };
+        auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_v + ((2 * (n / CB) + lh) * D + 32 * (n % CB) + lq) * 8); };
         h8 a[PF];
 #pragma unroll
         for (int n = 0; n < PF; ++n) a[n] = frag(n);
         PASA_FENCE();
 #pragma unroll
         for (int n = 0; n < NM2; ++n) {
-            const int cb = n / 8, kk = n % 8;
+            const int cb = n % CB, kk = n / CB;
             if (STRICT && kk == 0)
                 O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Pf[kk], (f16v)0.f, 0, 0, 0);
             else
                 O[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Pf[kk], O[cb], 0, 0, 0);
             PASA_FENCE();
-            hook(n);
             if (n + PF < NM2) a[n % PF] = frag(n + PF);
             PASA_FENCE();
         }
     };
-    auto no_hook = [](int) {};
 
     for (int j = 0; j <= J_wg; ++j) {
         // =========================== matrix part M(j) ===========================
@@ -611,37 +599,16 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         const bool diag = (CAUSAL && (j * T + T - 1 > pos_w0)) || tail;   // tile j needs the mask for this wave
         __builtin_amdgcn_s_setprio(1);
         // ---- pending product of tile j-1 ----
-        if (do_g2) {
-            gemm2(j - 1, no_hook);
-        }
+        if (do_g2) gemm2(j - 1);
         // ---- S'(j) ----
-        if (do_g1) {
-            if (STRICT) {
-                // the fp16 combination of the product just finished is left to the vector part: hooked behind these
-                // MFMAs (branch-free, as a hook must be) it was slower
-                gemm1(j, no_hook);
-            } else if (EARLY_MAX && !diag && !tail) {
-                gemm1(j, [&](int n) {      // the maximum of a finished 32-key block behind the MFMAs of the next one
-                    const int kb = n / KS - 1, ks = n % KS;
-                    if (kb < 0) return;
-                    constexpr int PER = 16 / KS;
-                    float macc = ks ? epm[kb] : -__builtin_inff();
-#pragma unroll
-                    for (int i = ks * PER; i < (ks + 1) * PER; ++i) macc = __builtin_fmaxf(macc, S[kb][i]);
-                    asm volatile("" : "+v"(macc));    // stays behind this MFMA (see above)
-                    epm[kb] = macc;
-                });
-                max_ready = true;
-            } else {
-                max_ready = false;
-                gemm1(j, no_hook);
-            }
-        }
+        if (do_g1) gemm1(j);
         __builtin_amdgcn_s_setprio(0);
         if (grp == 1) drain_copies();
         __syncthreads();
-        const int sg_mine = grp ? 2 * j + 2 : 2 * j;          // the even slot whose copies this wave issues now
-        if (!(j < J_w)) issue_slot(sg_mine);                  // no vector part to spread them over
+        // This wave's share of the tile copies first: they have the whole vector part to land (issued later, among the
+        // exponentials, their latency showed at the drain before the next barrier: 3.8 % of the kernel's cycles).
+        issue_slot(grp ? 2 * j + 2 : 2 * j);
+        PASA_FENCE();
 
         // =========================== vector part V(j) ===========================
         if (j < J_w) {
@@ -718,10 +685,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             float pm[4];
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) {
-                if (EARLY_MAX && kb < 3 && max_ready) {
-                    pm[kb] = epm[kb];
-                    continue;
-                }
                 if (STRICT) {
                     h2 mm = Sh[kb][0];
 #pragma unroll
@@ -851,12 +814,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3)] = p2[0];
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
                         pl[kb] = STRICT ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
-                    }
-                    {   // the copies are spread over the exponentials
-                        PASA_FENCE();
-#pragma unroll
-                        for (int idx = kb * (2 * CPW) / 4; idx < (kb + 1) * (2 * CPW) / 4; ++idx) issue_copy(sg_mine, idx);
-                        PASA_FENCE();
                     }
                 }
                 lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
