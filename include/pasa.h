@@ -96,7 +96,10 @@ int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
 /* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes: shifted keys K' and re-tiled values, both fp16
  * (4*B*Hkv*ceil(N/128)*128*d bytes), then one fp16 shift vector per key tile (2*B*Hkv*ceil(N/128)*d bytes, rounded up
  * to a multiple of 256; written and read by PASA_DIRECT only), then one 64-bit counter per (batch, KV head) (8*B*Hkv
- * bytes, rounded up to a multiple of 256; used by pasa_attn_fwd_adaptive only).  Returns 0 if the sizes are invalid. */
+ * bytes, rounded up to a multiple of 256; used by pasa_attn_fwd_adaptive only), then for every (batch, KV head) and
+ * group of 16 key tiles the per-channel means of the rounded K' of those tiles as fp16 pairs (64*d bytes per group,
+ * B*Hkv*ceil(ceil(N/128)/16) groups; written and read by PASA_MIXED only, which takes the pseudo-average of Eq. (14)
+ * as the query times that mean, Eq. (12)).  Returns 0 if the sizes are invalid. */
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,

@@ -95,7 +95,8 @@ double pasa_optimal_beta(double beta0, int n, int tp)
 namespace {
 
 // Workspace layout: the K'/V tiles, then (used by PASA_DIRECT only) one fp16 shift vector of d halfs per tile, then
-// (used by the adaptive entry point only) one 64-bit overflow counter per (batch, KV head).
+// (used by the adaptive entry point only) one 64-bit overflow counter per (batch, KV head), then (used by PASA_MIXED
+// only) one mean block of 32 x d halfs per 16 key tiles.
 size_t tiles_bytes(int B, int Hkv, int N, int d)
 {
     const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
@@ -114,6 +115,17 @@ size_t group_counter_bytes(int B, int Hkv)
     return ((size_t)8 * (size_t)B * (size_t)Hkv + 255) / 256 * 256;
 }
 
+size_t kmean_bytes(int B, int Hkv, int N, int d)
+{
+    const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;
+    return (size_t)B * (size_t)Hkv * ((ntile + 15) / 16) * 64 * (size_t)d;     // a multiple of 256
+}
+
+size_t kmean_offset(int B, int Hkv, int N, int d)
+{
+    return tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d) + group_counter_bytes(B, Hkv);
+}
+
 }  // namespace
 
 extern "C" {
@@ -121,7 +133,7 @@ extern "C" {
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
 {
     if (check_shape(B, Hq, Hkv, N, d) != PASA_OK) return 0;
-    return tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d) + group_counter_bytes(B, Hkv);
+    return kmean_offset(B, Hkv, N, d) + kmean_bytes(B, Hkv, N, d);
 }
 
 }  // extern "C"
@@ -155,7 +167,7 @@ int shift_keys_common(const void* k, void* kprime, int B, int Hkv, int N, int d,
     if (shift_mode == PASA_PREP_DIRECT && (k0out == nullptr || !aligned(k0out, 16) || k0out == kprime || k0out == k))
         return PASA_EINVAL;
     const hipError_t e = pasa_launch_prep(k, nullptr, nullptr, kprime, B, Hkv, N, d, c1, c2, shift_mode, 0, k0out,
-                                          nullptr, static_cast<hipStream_t>(stream));
+                                          nullptr, nullptr, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
 
@@ -256,8 +268,9 @@ int prepare_kv_impl(const void* k, const void* v, int B, int Hkv, int N, int d, 
     if (st != PASA_OK) return st;
     const int mode = pr.variant == PASA_DIRECT ? PASA_PREP_DIRECT : pr.matrix_mode ? PASA_PREP_MATRIX : PASA_PREP_MEAN;
     void* k0out = static_cast<char*>(workspace) + tiles_bytes(B, Hkv, N, d);
+    void* kmean = pr.variant == PASA_MIXED ? static_cast<char*>(workspace) + kmean_offset(B, Hkv, N, d) : nullptr;
     const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, mode, pr.io_bf16,
-                                          k0out, pr.gate, static_cast<hipStream_t>(stream));
+                                          k0out, kmean, pr.gate, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
 
@@ -301,6 +314,7 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     PasaLaunch p;
     p.q = q; p.ws = workspace; p.o = o;
     p.k0 = static_cast<const char*>(workspace) + tiles_bytes(B, Hkv, N, d);
+    p.kmean = static_cast<const char*>(workspace) + kmean_offset(B, Hkv, N, d);
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.d = d;
     p.Nq = Nq; p.row0 = causal ? row0 : 0;
     p.causal = causal;

@@ -14,6 +14,7 @@ struct PasaLaunch {
     const void* ws;   // per (batch, KV head, key tile): shifted-key tile then value tile, fragment-major layout
     void* o;
     const void* k0;   // PASA_K_DIRECT: per (batch, KV head, key tile) the fp16 shift vector, d halfs each
+    const void* kmean;  // PASA_K_MIXED: per (batch, KV head, 16 key tiles) the mean block, 32 x d halfs
     int B, Hq, Hkv, N, d;   // N: keys
     int Nq, row0;           // query rows given, and the sequence position of the first of them
     int causal;
@@ -37,9 +38,11 @@ struct PasaLaunch {
 // PASA_PREP_MATRIX: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
 //                   matrix a I + b (J - I) when beta carries a - b and kscale carries b (N % 128 == 0 only).
 // PASA_PREP_DIRECT: k0 = fp16(beta * tile mean) goes to k0out ([B, Hkv, tiles, d]) and K' = fp16((K - k0) * kscale).
+// kmean_out != nullptr: also the mean blocks of the rounded K' ([B, Hkv, ceil(tiles/16), 32, d] halfs) that
+// PASA_K_MIXED reads.
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
-                            void* k0out, const unsigned long long* gate, hipStream_t stream);
+                            void* k0out, void* kmean_out, const unsigned long long* gate, hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);
 

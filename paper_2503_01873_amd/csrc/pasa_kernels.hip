@@ -18,6 +18,10 @@
 //
 // Workspace: for every (batch, KV head, key tile) the K' tile followed by the V tile, so that one tile pair is
 // one contiguous block that is copied to LDS verbatim with direct global->LDS loads, double buffered.
+// For PASA_K_MIXED also, per (batch, KV head) and group of 16 key tiles, one "mean block": the per-channel mean over
+// 128 key slots of the rounded K' of each of the 16 tiles, split into an fp16 high and an fp16 low part (times 2^11), laid out
+// as a 32-row A operand (see pasa_prep_kv) -- by Eq. (12), (14) the pseudo-average of a score row is the query
+// times that mean, which the main kernel takes for 16 tiles at a time on the matrix core.
 // Tile layouts (one tile = 128 keys x D channels, fp16, 16-byte chunks):
 //   K' tile: chunk index (c/8)*128 + n         holds channels 8*(c/8) .. +7 of key n
 //   V  tile: chunk index ((n/16)*2 + h)*D + c  holds, for channel c, the 8 keys 16*(n/16) + {4h..4h+3, 8+4h..8+4h+3}
@@ -97,6 +101,7 @@ template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
                                                     _Float16* __restrict__ wsout,
                                                     _Float16* __restrict__ plain_out, _Float16* __restrict__ k0out,
+                                                    _Float16* __restrict__ kmean_out,
                                                     int N, int ntile, double beta, double kscale, int shift_mode,
                                                     int in_bf16, const unsigned long long* gate)
 {
@@ -195,6 +200,7 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     double mean[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) mean[e] = colv[8 * c8 + e];
+    double rs[8] = {0, 0, 0, 0, 0, 0, 0, 0};     // column sums of the ROUNDED K' over this thread's keys (exact in fp64)
 #pragma unroll
     for (int i = 0; i < KPT; ++i) {
         const int n = kl + KL * i;
@@ -216,12 +222,52 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
                 r = __dmul_rn(df, kscale);
             }
             out[e] = n < nvalid ? double_to_half_rn(r) : (_Float16)0;   // padding keys: exact zeros
+            rs[e] += (double)out[e];
         }
         if (plain_out != nullptr) {
             if (n < nvalid) *reinterpret_cast<h8*>(plain_out + src_off + (size_t)n * D + ch0) = out;
         } else {
             *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)(ch0 / 8) * T + n) * 8) = out;
         }
+    }
+    if (kmean_out == nullptr) return;
+
+    // ---- mean block: column sum of the rounded K' / 128 (an exact scaling), as an fp16 pair hi + lo ----
+    // A block serves 16 consecutive key tiles and is a 32-row x D A operand in the K' tile's chunk order (chunk
+    // (c/8)*32 + row holds channels 8*(c/8)..+7 of row `row`).  Tile t of the group has its high part in row
+    // 8*(t/4) + t%4 and its low part four rows further down: in the 32x32 accumulator layout the first kind of row
+    // lands in lanes 0-31 and the second in lanes 32-63 of the same accumulator register.
+    __syncthreads();                       // psum is reused
+#pragma unroll
+    for (int e = 0; e < 8; ++e) psum[kl][8 * c8 + e] = rs[e];
+    __syncthreads();
+    {
+        const int c = tid % DB, part = tid / DB;
+        double acc = 0;
+        for (int r = part; r < KL; r += PARTS) acc += psum[r][c];
+        psum2[part][c] = acc;
+    }
+    __syncthreads();
+    if (tid < DB) {
+        double tot = 0;
+#pragma unroll
+        for (int r = 0; r < PARTS; ++r) tot += psum2[r][tid];
+        const double m128 = tot * 0.0078125;                 // 2^-7: exact
+        // the low part is stored times 2^11 (undone when the two products are added): unscaled it is an fp16
+        // subnormal for every mean below 0.125, and the matrix core reads those as zero
+        const _Float16 hi = double_to_half_rn(m128);
+        const _Float16 lo = double_to_half_rn((m128 - (double)hi) * 2048.0);
+        const int nblk = (ntile + 15) / 16;
+        const int t16 = t & 15, row = 8 * (t16 >> 2) + (t16 & 3), c = cg * DB + tid;
+        _Float16* blk = kmean_out + ((head * (size_t)nblk + (size_t)(t >> 4)) * 32) * D;
+        blk[((size_t)(c / 8) * 32 + row) * 8 + (c % 8)] = hi;
+        blk[((size_t)(c / 8) * 32 + row + 4) * 8 + (c % 8)] = lo;
+        if (t == ntile - 1)                                   // rows of the tiles that do not exist: zeros
+            for (int u = t16 + 1; u < 16; ++u) {
+                const int ru = 8 * (u >> 2) + (u & 3);
+                blk[((size_t)(c / 8) * 32 + ru) * 8 + (c % 8)] = (_Float16)0;
+                blk[((size_t)(c / 8) * 32 + ru + 4) * 8 + (c % 8)] = (_Float16)0;
+            }
     }
 }
 
@@ -238,6 +284,14 @@ __device__ inline void halves32(float x, float& lo, float& hi)
     lo = x;
     hi = x;
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(lo), "+v"(hi));
+}
+// lanes 32-63 of a <-> lanes 0-31 of b.  Through the builtin, so that the compiler sees the reads: the operands here
+// come straight from an MFMA, whose result registers must not be read before the instruction has written them all.
+__device__ inline void swap32(float& a, float& b)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
 }
 __device__ inline float sum32(float x)
 {
@@ -335,7 +389,8 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
-              const _Float16* __restrict__ k0, int Hq, int Hkv, int Nq, int row0, int N, int nqt, float inva, float scale,
+              const _Float16* __restrict__ k0, const _Float16* __restrict__ kmean, int Hq, int Hkv, int Nq, int row0, int N,
+              int nqt, float inva, float scale,
               int io_bf16,
               unsigned long long* ovf_s, unsigned long long* nonfinite_o, unsigned long long* ovf_group,
               const unsigned long long* gate)
@@ -347,6 +402,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     constexpr bool STRICT = (VAR == PASA_K_STRICT16);
     constexpr bool NAIVE = (VAR == PASA_K_NAIVE16);
     constexpr bool DIRECT = (VAR == PASA_K_DIRECT);               // bias added back as scale * (q . k0), no pseudo-average
+    // MIXED takes the pseudo-average as q . colmean(K') (Eq. (12), (14)) on the matrix core, 16 tiles at a time,
+    // instead of summing 128 scores per row and tile on the vector unit
+    constexpr bool MSBAR = (VAR == PASA_K_MIXED);
+    constexpr int KM_BYTES = 64 * D;                            // one mean block: 32 rows x D halfs
+    constexpr int SB_OFF = 4 * (T * D * 2) + KM_BYTES;          // per-wave [16 tiles][32 rows] floats behind it
     constexpr int KT_BYTES = T * D * 2;                         // one K' (or V) tile
     constexpr int TILE_BYTES = 2 * KT_BYTES;                    // workspace stride: K' tile then V tile
     constexpr int CPW = KT_BYTES / 1024 / 8;                    // 1 KiB copies per wave per K' (or V) tile
@@ -428,6 +488,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             __builtin_amdgcn_raw_ptr_buffer_load_lds(k0buf, (__attribute__((address_space(3))) void*)(smem + 4 * KT_BYTES + (j & 1) * 256),
                                                      4, lane * 4, j * D * 2, 0, 0);
     };
+    // mean blocks of this (batch, KV head): block g serves tiles 16g .. 16g+15; one 1 KiB piece per wave (D = 64: waves 0-3)
+    const int nblk16 = (ntile + 15) >> 4;
+    const __amdgpu_buffer_rsrc_t kmbuf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<_Float16*>(MSBAR ? kmean + ((size_t)(b * Hkv + hk) * nblk16) * (32 * D) : q), 0, MSBAR ? nblk16 * KM_BYTES : 0,
+        0x00020000);
+    auto issue_kmean = [&](int g) {
+        if (MSBAR && wave * 1024 < KM_BYTES && g < nblk16)
+            copy_1k_to_lds<0>(kmbuf, g * KM_BYTES + wave * 1024, smem + 4 * KT_BYTES + wave * 1024, lane);
+    };
     auto issue_k = [&](int j) {
         issue_k0(j);
         const int src = j * TILE_BYTES;
@@ -436,6 +505,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(wsbuf, src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
     };
     issue_k(0);
+    issue_kmean(0);
 
     // Q fragments: B operand, lane (query lq, half lh) holds channels 16*ks + 8*lh .. +7
     h8 Qf[KS];
@@ -598,6 +668,24 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         const bool tail = (tail_keys != 0) && (j == ntile - 1); // ragged last tile: padding keys are masked
         const bool diag = (CAUSAL && (j * T + T - 1 > pos_w0)) || tail;   // tile j needs the mask for this wave
         __builtin_amdgcn_s_setprio(1);
+        // ---- pseudo-averages of the next 16 tiles: rows of A are the high and low parts of the tiles' mean keys ----
+        if (MSBAR && (j & 15) == 0 && do_g1) {
+            const _Float16* lds_km = reinterpret_cast<const _Float16*>(smem + 4 * KT_BYTES);
+            f16v acc = (f16v)0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const h8*>(lds_km + ((2 * ks + lh) * 32 + lq) * 8),
+                                                             Qf[ks], acc, 0, 0, 0);
+            // lanes 0-31 hold q . hi of tile i in element i, lanes 32-63 q . lo of the same tile; after the exchange
+            // element i + 8 -> i the sum is tile i in lanes 0-31 and tile i + 8 in lanes 32-63
+            float* sb = reinterpret_cast<float*>(smem + SB_OFF + wave * 2048);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float x = acc[i], y = acc[i + 8];
+                swap32(x, y);
+                sb[(i + 8 * lh) * 32 + lq] = x + y * 0.00048828125f;      // low parts are stored times 2^11
+            }
+        }
         // ---- pending product of tile j-1 ----
         if (do_g2) gemm2(j - 1);
         // ---- S'(j) ----
@@ -608,6 +696,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         // This wave's share of the tile copies first: they have the whole vector part to land (issued later, among the
         // exponentials, their latency showed at the drain before the next barrier: 3.8 % of the kernel's cycles).
         issue_slot(grp ? 2 * j + 2 : 2 * j);
+        if (MSBAR && (j & 15) == 8) issue_kmean((j >> 4) + 1);   // read from M(16 * ((j >> 4) + 1)) on, free since M(j - 8)
         PASA_FENCE();
 
         // =========================== vector part V(j) ===========================
@@ -647,7 +736,11 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             }
             // ---- pseudo-average over all 128 keys of the tile (before masking) ----
             float sbar = 0.f;
-            if (!NAIVE && !DIRECT) {
+            if (MSBAR) {
+                // stored per 128 key slots; a ragged last tile divides by its own key count
+                const float v = reinterpret_cast<const float*>(smem + SB_OFF + wave * 2048)[(j & 15) * 32 + lq];
+                sbar = tail ? v * ((float)T * inv_tail) : v;
+            } else if (!NAIVE && !DIRECT) {
                 float ps[4];
 #pragma unroll
                 for (int kb = 0; kb < 4; ++kb) {
@@ -813,7 +906,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         const h2 p2 = pack_rn(e0, e1);
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3)] = p2[0];
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
-                        pl[kb] = STRICT ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
+                        pl[kb] = (STRICT || MSBAR) ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
                     }
                 }
                 lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
@@ -879,7 +972,7 @@ template <int D, int VAR, bool CAUSAL, bool INSTR>
 hipError_t launch_fwd(const PasaLaunch& p)
 {
     constexpr int RWG = 256;
-    constexpr int LDS_BYTES = 4 * (T * D * 2) + (VAR == PASA_K_DIRECT ? 512 : 0);
+    constexpr int LDS_BYTES = 4 * (T * D * 2) + (VAR == PASA_K_DIRECT ? 512 : 0) + (VAR == PASA_K_MIXED ? 64 * D + 8 * 2048 : 0);
     const int nqt = (p.Nq + RWG - 1) / RWG;
     const dim3 grid((unsigned)(nqt * p.Hq * p.B));
     auto kern = pasa_fwd<D, VAR, CAUSAL, INSTR>;
@@ -887,7 +980,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
                                        LDS_BYTES);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
-                       (_Float16*)p.o, (const _Float16*)p.k0, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
+                       (_Float16*)p.o, (const _Float16*)p.k0, (const _Float16*)p.kmean, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
                        p.nonfinite_o, p.overflow_group, p.gate);
     return hipGetLastError();
 }
@@ -917,16 +1010,16 @@ hipError_t launch_fwd_d(const PasaLaunch& p)
 
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
-                            void* k0out, const unsigned long long* gate, hipStream_t stream)
+                            void* k0out, void* kmean_out, const unsigned long long* gate, hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
     const dim3 grid((unsigned)((size_t)B * Hkv * ntile), (v != nullptr ? 2u : 1u) * PASA_PREP_SPLIT);   // y: key channel groups, then value key groups
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, (_Float16*)kmean_out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, (_Float16*)kmean_out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
     return hipGetLastError();
 }
 

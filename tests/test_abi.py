@@ -75,12 +75,14 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
 
 
 def test_workspace_size():
-    # K'/V tiles, then one fp16 shift vector per key tile (rounded up to 256 bytes)
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256
+    # K'/V tiles, then one fp16 shift vector per key tile (rounded up to 256 bytes), then the counters of the adaptive
+    # start (256 bytes here), then one mean block of 32 x d halfs per (KV head, 16 key tiles)
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256 + 4 * 4 * 64 * 128
     assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 96) == 0
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256   # ragged last tile is padded
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64 + 512 + 256
-    assert P.pasa_attn_fwd_workspace(1, 1, 1, 128, 64) == 4 * 128 * 64 + 256 + 256
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128)   # ragged last tile is padded
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64 + 512 + 256 + 4 * 64 * 64
+    assert P.pasa_attn_fwd_workspace(1, 1, 1, 128, 64) == 4 * 128 * 64 + 256 + 256 + 64 * 64
+    assert P.pasa_attn_fwd_workspace(1, 1, 1, 17 * 128, 64) == 4 * 17 * 128 * 64 + 2 * 17 * 64 + 128 + 256 + 2 * 64 * 64
     assert P.pasa_attn_fwd_workspace(1, 28, 5, 8192, 128) == 0
 
 
@@ -133,7 +135,8 @@ def test_other_entry_points_reject_bad_arguments():
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 0}) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "row0": -1}) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 262144 + 1}) == 2
-    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": 4 * 2 * 256 * 64 + 512 - 1}) == 4
+    assert P.pasa_attn_fwd_workspace(1, 4, 2, 256, 64) == 4 * 2 * 256 * 64 + 512 + 256 + 2 * 64 * 64
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": P.pasa_attn_fwd_workspace(1, 4, 2, 256, 64) - 1}) == 4
     assert P.pasa_shift_keys_direct(K, O, 0, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_shift_keys_direct(K, O, O, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "N": 200, "shift_mode": P.SHIFT_MATRIX}) == 2
