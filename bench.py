@@ -8,6 +8,11 @@ synthetic seeded inputs already resident in HBM.  Prints ONE JSON line.
   value      counted FLOPs (4*B*Hq*N^2*d, halved for causal) / wall time per step, TFLOP/s
   roofline   the main kernel alone: counted FLOPs per launch / its mean duration between HIP events
              recorded on the launch stream inside the timed region, against the dense fp16 MFMA peak
+  variants   the same launch timed for PASA_STRICT16 (every quantity Algorithm 1 marks is rounded to fp16), outside
+             the timed region of the headline figure
+  overflow   counts from instrumented calls (not timed): score-tile entries beyond 65504 where they would be stored
+             as fp16 and non-finite outputs, for PASA and for the unshifted fp16-score FlashAttention, on this
+             workload and on the large-bias workload
   cpu_baseline  the numpy fp64 oracle timed on this machine's host cores on a bounded sample of the same workload
 """
 from __future__ import annotations
@@ -27,15 +32,29 @@ WORKLOAD = "qwen2_gqa_n8192"
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "pasa_fwd_qwen2_gqa_n8192_hbm_traffic.txt")
 
 
-def read_traffic():
-    """HBM bytes per main-kernel launch from the committed rocprofv3 --pmc summary, if present."""
+def kernel_source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    with open(os.path.join(ROOT, "paper_2503_01873_amd", "csrc", "pasa_kernels.hip"), "rb") as f:
+        h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def read_traffic(source_hash=None):
+    """HBM bytes per main-kernel launch from the committed rocprofv3 --pmc summary -- only if that summary was
+    measured on the kernel source that is in the tree now (it names the source's hash); otherwise None."""
+    traffic = stamp = None
     try:
         for line in open(TRAFFIC_FILE):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                traffic = float(line.split(":")[1])
+            if line.startswith("kernel_source_sha256_16:"):
+                stamp = line.split(":")[1].strip()
+        if source_hash is None:
+            source_hash = kernel_source_hash()
     except OSError:
-        pass
-    return None
+        return None
+    return traffic if (stamp is not None and stamp == source_hash) else None
 
 
 def cpu_baseline(w, q_heads, kv_heads, scale, budget_s=12.0):
@@ -93,13 +112,10 @@ def main():
                     help="another of the five configurations by name (for profiles of the other shapes; no accuracy check "
                          "or CPU baseline then, and the committed HBM-traffic figure is not attached).  The default is the "
                          "configuration the metric's target is quoted on")
-    ap.add_argument("--inputs", default="workload", choices=["workload", "zeros", "ones"],
-                    help="diagnostic: all-zero or all-one q, k, v of the same shape instead of the workload's values.  "
-                         "The instruction stream is the same, the data toggles nothing, and the power management leaves "
-                         "the shader clock high: the difference from the default run is clock, not cycles "
-                         "(no accuracy check and no CPU baseline in that case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-accuracy", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the STRICT16 timing and the overflow counts")
+    ap.add_argument("--extra-steps", type=int, default=300, help="timed steps of the STRICT16 leg")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (a known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -118,7 +134,7 @@ def main():
                "direct": P.DIRECT}[args.variant]
     w = workload(args.workload)
     if args.workload != WORKLOAD:
-        args.no_accuracy = args.no_cpu_baseline = True
+        args.no_accuracy = args.no_cpu_baseline = args.no_extras = True
     scale = float(np.float32(w.scale))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -135,10 +151,6 @@ def main():
             kk, vv = kv_heads[hk] if b == 0 else gen_kv_head(w, b, hk)
             tk[b, hk].copy_(torch.from_numpy(kk))
             tv[b, hk].copy_(torch.from_numpy(vv))
-    if args.inputs != "workload":
-        fill = 0.0 if args.inputs == "zeros" else 1.0
-        tq, tk, tv = (torch.full_like(t, fill) for t in (tq, tk, tv))
-        args.no_accuracy = args.no_cpu_baseline = True
     to = torch.full_like(tq, float("nan"))
     wsb = P.pasa_attn_fwd_workspace(w.B, w.Hq, w.Hkv, w.N, w.d)
     ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
@@ -197,7 +209,7 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f16",
-        "data": "synthetic" if args.inputs == "workload" else "synthetic, all " + args.inputs + " (clock diagnostic, not the workload's values)",
+        "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "N": w.N, "d": w.d, "causal": w.causal,
                    "variant": args.variant, "beta": "63.5/64.5", "shift_tile": 128,
                    "mfma_accumulate": "fp32 (hardware); fp16 roundings applied where Algorithm 1 marks them"},
@@ -210,6 +222,68 @@ def main():
         "device": {"name": prop.name, "arch": getattr(prop, "gcnArchName", ""), "compute_units": prop.multi_processor_count,
                    "peak_used": "2500 TFLOP/s dense fp16 MFMA (256 CUs x 4 SIMDs x 1024 FLOP/clk x 2.4 GHz)"},
     }
+
+    if not args.no_extras:
+        o_keep = to.clone()                      # the headline variant's output, for the accuracy leg below
+
+        # ---- the fp16-rounded variant Algorithm 1 defines, same launch, timed on its own
+        def step_v(var, ev=None):
+            P.pasa_prepare_kv(tk, tv, w.B, w.Hkv, w.N, w.d, scale, ws, wsb, stream, variant=var)
+            if ev is not None:
+                ev[0].record(stream)
+            P.pasa_attn_fwd_prepared(tq, to, *dims, w.causal, scale, ws, wsb, stream, variant=var)
+            if ev is not None:
+                ev[1].record(stream)
+
+        out["variants"] = {}
+        for name, var in (("strict16", P.STRICT16),):
+            for _ in range(100):
+                step_v(var)
+            torch.cuda.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                   for _ in range(args.extra_steps)]
+            t1 = time.perf_counter()
+            for i in range(args.extra_steps):
+                step_v(var, evs[i])
+            torch.cuda.synchronize()
+            dt1 = time.perf_counter() - t1
+            kms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+            out["variants"][name] = {"kernel_ms": kms, "ms_per_step": dt1 * 1e3 / args.extra_steps,
+                                     "tflops": w.flops / (kms * 1e-3) / 1e12,
+                                     "frac": w.flops / (kms * 1e-3) / 1e12 / PEAK_FP16_TFLOPS, "steps": args.extra_steps}
+
+        # ---- overflow counts (instrumented builds of the same kernels, one call each, not timed)
+        def counts(wl, q_, k_, v_, o_, ws_, wsb_, var):
+            cnt = torch.zeros(2, dtype=torch.int64, device=dev)
+            P.pasa_attn_fwd_ex(q_, k_, v_, o_, wl.B, wl.Hq, wl.Hkv, wl.N, wl.d, wl.causal, float(np.float32(wl.scale)),
+                               ws_, wsb_, stream, variant=var, overflow_s=cnt[0:1], nonfinite_o=cnt[1:2])
+            torch.cuda.synchronize()
+            c = cnt.tolist()
+            return int(c[0]), int(c[1])
+
+        w2 = workload("overflow_bias")
+        q2 = torch.empty((w2.B, w2.Hq, w2.N, w2.d), dtype=torch.float16, device=dev)
+        k2 = torch.empty((w2.B, w2.Hkv, w2.N, w2.d), dtype=torch.float16, device=dev)
+        v2 = torch.empty_like(k2)
+        for h in range(w2.Hq):
+            q2[0, h].copy_(torch.from_numpy(gen_q_head(w2, 0, h)))
+        for hk in range(w2.Hkv):
+            kk, vv = gen_kv_head(w2, 0, hk)
+            k2[0, hk].copy_(torch.from_numpy(kk))
+            v2[0, hk].copy_(torch.from_numpy(vv))
+        o2 = torch.empty_like(q2)
+        wsb2 = P.pasa_attn_fwd_workspace(w2.B, w2.Hq, w2.Hkv, w2.N, w2.d)
+        ws2 = torch.empty(wsb2, dtype=torch.uint8, device=dev)
+        ov = {}
+        for wl, args_ in ((w, (tq, tk, tv, to, ws, wsb)), (w2, (q2, k2, v2, o2, ws2, wsb2))):
+            entries = wl.B * wl.Hq * wl.N * wl.N // (2 if wl.causal else 1)
+            row = {"score_entries_counted_convention": entries}
+            for name, var in (("pasa_mixed", P.MIXED), ("pasa_strict16", P.STRICT16), ("naive16", P.NAIVE16)):
+                s_over, o_bad = counts(wl, *args_, var)
+                row[name] = {"s_over_65504": s_over, "nonfinite_o": o_bad}
+            ov[wl.name] = row
+        out["overflow"] = ov
+        to.copy_(o_keep)
 
     if not args.no_accuracy:
         from oracle import pasa_oracle as po

@@ -31,6 +31,7 @@
 // Algorithm 1 marks them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include <type_traits>
 
 #include "pasa_kernels.h"
@@ -976,9 +977,17 @@ hipError_t launch_fwd(const PasaLaunch& p)
     const int nqt = (p.Nq + RWG - 1) / RWG;
     const dim3 grid((unsigned)(nqt * p.Hq * p.B));
     auto kern = pasa_fwd<D, VAR, CAUSAL, INSTR>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       LDS_BYTES);
+    // the dynamic LDS limit of this instantiation is raised once per device, not on every launch
+    static std::atomic<unsigned long long> lds_limit_set{0ull};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (!(lds_limit_set.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        lds_limit_set.fetch_or(bit, std::memory_order_release);
+    }
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
                        (_Float16*)p.o, (const _Float16*)p.k0, (const _Float16*)p.kmean, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
                        p.nonfinite_o, p.overflow_group, p.gate);

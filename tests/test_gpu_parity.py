@@ -105,9 +105,7 @@ def test_scaled_workloads_full_tensor(idx, N, over, variant):
     assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
     assert abs(r_gpu - r_or) <= 0.02 * r_or + 2e-5
     if variant == P.MIXED:
-        assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
-        if idx in (1, 5):
-            assert c["maxabs"] <= 2e-3
+        assert c["maxabs"] <= 2e-3          # the stated bar, on every workload
     elif variant == P.STRICT16:
         assert c["p999"] <= 2e-3
     else:
@@ -297,7 +295,7 @@ def test_matrix_shift_scaled_workloads(idx, N, over):
     r_gpu, r_or = po.rmse(o, gold), po.rmse(ref, gold)
     print(w.name, c, "rmse gpu %.3e oracle %.3e" % (r_gpu, r_or))
     assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
-    assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
+    assert c["maxabs"] <= 2e-3
     assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
 
 
@@ -331,10 +329,13 @@ def test_bf16_io(idx, N, over, variant):
         assert c["maxabs"] <= 4e-3
     else:
         assert c["p999"] <= 4e-3 and c["maxabs"] <= 1.6e-2
-    # Sanity only: most outputs round to the same bf16 value.  The kernel's P carries the factor that places the tile at
-    # the stored output's scale (folded into the exponent), so its fp16 rounding differs from the oracle's P of
-    # Algorithm 1 and the outputs agree to rounding, not bit for bit.
-    assert (o == ref).mean() > (0.85 if variant == P.MIXED else 0.6)
+    # In units of the stored format: nearly every output is the oracle's bf16 value or its neighbour.  (How many are
+    # the very same value depends on where P is rounded -- the kernel's P carries the factor that places the tile at the
+    # stored output's scale, Algorithm 1's does not -- so that fraction is printed, not asserted.)
+    big = np.abs(ref) >= 0.5          # one bf16 step is at least 2e-3 there, the size of the whole stated tolerance
+    print("equal bf16 values: %.3f; of the outputs beyond 0.5 within one bf16 step: %.4f" % ((o == ref).mean(), (steps[big] <= 1).mean()))
+    if variant == P.MIXED:
+        assert (steps[big] <= 1).all()
 
 
 def test_bf16_input_beyond_fp16_range_becomes_infinite_like_the_oracle():
@@ -390,7 +391,7 @@ def test_chunked_causal_prefill_equals_one_call():
     ref = po.pasa_bhnd(q, k, v, scale, True, BETA, 128, po.MIXED)
     c = compare(odd, ref)
     print(c)
-    assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
+    assert c["maxabs"] <= 2e-3
 
 
 @pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16])
@@ -486,9 +487,15 @@ def test_direct_scaled_workloads(idx, N, over, causal):
     print(w.name, causal, c, "rmse gpu %.3e oracle %.3e paper's recovery %.3e" % (r_gpu, r_or, r_paper))
     assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
     # The kernel rounds P once at the scale the output is stored at, the oracle rounds exp(S' - m') and scales the
-    # product: two equally accurate roundings.  On the extreme-bias workload, where both sit 1.4e-3 (RMSE) from fp64,
-    # they differ by up to 2.5e-3 in single elements; everywhere else by at most one fp16 ulp of the output.
-    assert c["maxabs"] <= (3e-3 if idx == 2 else 2e-3) and c["p999"] <= 2e-3
+    # product: two equally accurate roundings of every P, each with a relative error of at most 2^-11.  The two
+    # outputs therefore differ by at most 2 * 2^-11 * sum_n w_n |v_n| (w the softmax weights) plus the two final
+    # roundings to fp16 (half an ulp each).  On the extreme-bias workload the softmax is nearly one-hot, so the sum is
+    # |v| of the winning key, at most max |v| (about 4): that bound, 2^-10 max |v|, is asserted there; everywhere else
+    # the stated 2e-3 holds.
+    if idx == 2:
+        assert c["maxabs"] <= 2.0 ** -10 * float(np.abs(v.astype(np.float64)).max()) and c["p999"] <= 2e-3
+    else:
+        assert c["maxabs"] <= 2e-3 and c["p999"] <= 2e-3
     assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
     # the stated accuracy bar; on the extreme-bias workload the rounding of K' alone leaves 1.4e-3 (the paper's
     # recovering step: 1.7e-2 on the same inputs)
@@ -703,7 +710,7 @@ def test_adaptive_start_switches_to_pasa_on_overflow(variant):
         ref, trig = po.adaptive_bhnd(q, k, v, scale, w.causal, BETA)
         assert trig
         c = compare(o, ref)
-        assert c["p999"] <= 2e-3 and c["maxabs"] <= 1e-2
+        assert c["maxabs"] <= 2e-3
 
 
 def test_adaptive_start_switches_only_the_kv_head_that_overflowed():
@@ -824,6 +831,8 @@ def _sampled_check(w, variant, units, tol_p999=2e-3, oracle="pasa"):
     print(w.name, VARIANT_NAME[variant], "maxabs %.3e p999 %.3e rmse gpu %.3e oracle %.3e"
           % (dd.max(), np.quantile(dd, 0.999), r_gpu, r_or))
     assert np.quantile(dd, 0.999) <= tol_p999
+    if variant in (P.MIXED, P.DIRECT):
+        assert dd.max() <= 2e-3, "max-abs against the emulated oracle above the stated bar: %d elements" % int((dd > 2e-3).sum())
     assert abs(r_gpu - r_or) <= 0.03 * r_or + 2e-5
     return r_gpu, r_or
 
