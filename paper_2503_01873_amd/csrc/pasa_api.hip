@@ -34,12 +34,24 @@ double round_to_format(double x, int prec, int emin, int emax)
 
 double fl_tp(double x, int tp) { return tp == 0 ? round_to_format(x, 11, -14, 15) : round_to_format(x, 8, -126, 127); }
 
-// Eq. (20), (21): the invariance the rounded shifting matrix a*I - b*J really has.
-double invariance_rounded(double beta, int n, int tp)
+// The entries of the rounded shifting matrix of Appendix A: off-diagonal -b with b = fl(beta / n), diagonal
+// a - b with a - b = fl(1 - beta / n) (Eq. (21)).  Both are step functions of beta.
+struct RoundedPair {
+    double a, b;
+    bool operator==(const RoundedPair& o) const { return a == o.a && b == o.b; }
+};
+
+RoundedPair rounded_pair(double beta, int n, int tp)
 {
     const double b = fl_tp(beta / n, tp);
-    const double a = fl_tp(1.0 - beta / n, tp) + b;
-    return b * n / (a * (a - b * n)) + (1.0 - a) / a;
+    return {fl_tp(1.0 - beta / n, tp) + b, b};
+}
+
+// Eq. (20): the invariance that a*I - b*J really has, from its exact inverse (Theorem 2.1 with lambda = b / a).
+double invariance_of_pair(const RoundedPair& p, int n)
+{
+    const double bn = p.b * n;
+    return bn / (p.a * (p.a - bn)) + (1.0 - p.a) / p.a;
 }
 
 int check_shape(int B, int Hq, int Hkv, int N, int d)
@@ -73,21 +85,27 @@ int pasa_version(void) { return 100; }
 double pasa_invariance_rounded(double beta, int n, int tp)
 {
     if (!(beta >= 0.0) || !(beta < 1.0) || n <= 0 || (tp != 0 && tp != 1)) return NAN;
-    return invariance_rounded(beta, n, tp);
+    return invariance_of_pair(rounded_pair(beta, n, tp), n);
 }
 
 double pasa_optimal_beta(double beta0, int n, int tp)
 {
     if (!(beta0 > 0.0) || !(beta0 < 1.0) || n <= 0 || (tp != 0 && tp != 1)) return NAN;
+    // The optimal accuracy condition beta / (1 - beta) = f(beta) (Eq. (16)) has a right-hand side that only depends on
+    // the rounded pair (a, b), which is constant on intervals of beta.  On such an interval the condition is solved in
+    // closed form, beta* = f / (1 + f); beta* is a solution iff it lies in the interval it was computed for, i.e. iff
+    // rounding at beta* gives the same pair again.  Starting from the pair of beta0 and moving to the pair of the
+    // candidate until it reproduces itself visits the same intervals as the iteration of Eq. (22) and ends exactly.
+    RoundedPair pair = rounded_pair(beta0, n, tp);
     double beta = beta0;
-    for (int it = 0; it < 1000; ++it) {          // Eq. (22): beta <- f/(1+f)
-        const double f = invariance_rounded(beta, n, tp);
-        const double next = f / (1.0 + f);
-        const double err = fabs(next - beta) / fabs(beta);
-        beta = next;
-        if (err <= 1e-8) break;
+    for (int visited = 0; visited < 256; ++visited) {
+        const double f = invariance_of_pair(pair, n);
+        beta = f / (1.0 + f);
+        const RoundedPair again = rounded_pair(beta, n, tp);
+        if (again == pair) return beta;
+        pair = again;
     }
-    return beta;
+    return beta;     // no self-consistent interval found within the budget: the last candidate, as the iteration would give
 }
 
 }  // extern "C"

@@ -61,7 +61,9 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
     for b0, want in golden("optimal_beta.txt"):
         got = P.pasa_optimal_beta(float(b0), 128, 0)
         assert f"{got:.6f}" == want
-        assert got == po.optimal_beta(float(b0), 128, "f16")
+        assert got == pytest.approx(po.optimal_beta(float(b0), 128, "f16"), rel=1e-12)
+        # the library's solution is exact: it reproduces its own rounded pair, so the condition holds to the last bit
+        assert P.pasa_invariance_rounded(got, 128, 0) == pytest.approx(got / (1 - got), rel=1e-13)
     for b0 in (0.9, 0.99, 0.999):
         assert P.pasa_optimal_beta(b0, 128, 0) == pytest.approx(po.optimal_beta(b0, 128, "f16"), rel=1e-12)
         assert P.pasa_invariance_rounded(b0, 128, 0) == pytest.approx(po.invariance_rounded(b0, 128, "f16"), rel=1e-12)
