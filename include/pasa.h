@@ -99,11 +99,22 @@ int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
  * bytes, rounded up to a multiple of 256; used by pasa_attn_fwd_adaptive only), then for every (batch, KV head) and
  * group of 16 key tiles the per-channel means of the rounded K' of those tiles as fp16 pairs (64*d bytes per group,
  * B*Hkv*ceil(ceil(N/128)/16) groups; written and read by PASA_MIXED only, which takes the pseudo-average of Eq. (14)
- * as the query times that mean, Eq. (12)).  Returns 0 if the sizes are invalid. */
+ * as the query times that mean, Eq. (12)); these regions together are pasa_attn_fwd_workspace_min().  Last comes the
+ * region of the key split: when a call would launch fewer than 192 workgroups (one per 256 query rows of a head) on the
+ * 256 compute units, the key tiles of every workgroup are divided among up to 16 workgroups in pieces of 16 tiles,
+ * each leaves per query row its unnormalised output (d floats) and two doubles (running sum, level), and a second
+ * kernel merges them with the log-sum-exp rule (the same algebra that lets the method run as ring attention, section
+ * 2.2).  The region is sized for a call with N query rows (at least 1 MiB, so that short query chunks can split);
+ * a call given less than that splits fewer ways or not at all, and one given less than pasa_attn_fwd_workspace_min()
+ * fails with PASA_EWORKSPACE.  Not used by PASA_STRICT16 (its fp16 state has no merge rule in Algorithm 1) nor by the
+ * adaptive entry point.  Returns 0 if the sizes are invalid. */
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 
+/* The part of the workspace every call needs (all regions but the key split's). */
+size_t pasa_attn_fwd_workspace_min(int B, int Hkv, int N, int d);
+
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
- * at least pasa_attn_fwd_workspace() bytes; contents on return are unspecified).  opts == NULL means
+ * pasa_attn_fwd_workspace() bytes -- at least pasa_attn_fwd_workspace_min(); contents on return are unspecified).  opts == NULL means
  * {beta = -1, PASA_MIXED, 128, NULL, NULL, PASA_SHIFT_MEAN, PASA_IO_F16}.  Performs no allocation. */
 int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
                      int B, int Hq, int Hkv, int N, int d, int causal, float scale,
@@ -113,8 +124,9 @@ int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o,
  * that forbid hipMalloc): pasa_attn_fwd_ex with its workspace in a fixed array of PASA_STATIC_WORKSPACE_BYTES of
  * device memory that belongs to the library (one copy per GPU the library is used on, held until the process ends).
  * Calls no hipMalloc / hipFree and no allocating routine.  PASA_EWORKSPACE if
- * pasa_attn_fwd_workspace(B, Hq, Hkv, N, d) exceeds PASA_STATIC_WORKSPACE_BYTES (e.g. B*Hkv*N*d > 8 Mi elements
- * for N % 128 == 0); otherwise arguments, options and errors as pasa_attn_fwd_ex.  The device that is current at
+ * pasa_attn_fwd_workspace_min(B, Hkv, N, d) exceeds PASA_STATIC_WORKSPACE_BYTES (e.g. B*Hkv*N*d > 8 Mi elements
+ * for N % 128 == 0; the key split uses what the fixed regions leave of the array); otherwise arguments, options and
+ * errors as pasa_attn_fwd_ex.  The device that is current at
  * the call must be the stream's.  The first call on a device looks the array's address up (no allocation, but make
  * it before a capture begins).  All calls on one GPU share the one array: calls that may overlap in time on one GPU
  * (different streams, or different threads) race on it and must be serialised by the caller; the array keeps the
@@ -129,7 +141,8 @@ int pasa_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
  * pre-processing loop (key shift, Eq. (11)) and re-tiles K' and V into `workspace`;
  * pasa_attn_fwd_prepared runs the main loops of Algorithm 1 against such a workspace.  Both calls must be
  * given the same B, Hkv, N, d, scale and opts (beta, variant); pasa_attn_fwd_prepared does not read k or v.
- * Same argument rules, workspace size and error codes as pasa_attn_fwd_ex. */
+ * It reads the prepared regions and may write the key-split region at the end of the workspace, so calls that use
+ * one workspace must not overlap in time.  Same argument rules, workspace size and error codes as pasa_attn_fwd_ex. */
 int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, float scale,
                     const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
 int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
     L.pasa_attn_fwd.restype = ci
     L.pasa_attn_fwd_workspace.argtypes = [ci, ci, ci, ci, ci]
     L.pasa_attn_fwd_workspace.restype = sz
+    L.pasa_attn_fwd_workspace_min.argtypes = [ci, ci, ci, ci]
+    L.pasa_attn_fwd_workspace_min.restype = sz
     L.pasa_attn_fwd_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_attn_fwd_ex.restype = ci
     L.pasa_attn_fwd_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp]
@@ -125,6 +127,10 @@ def pasa_invariance_rounded(beta: float, n: int, tp: int = 0) -> float:
 
 def pasa_attn_fwd_workspace(B, Hq, Hkv, N, d) -> int:
     return lib().pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
+
+
+def pasa_attn_fwd_workspace_min(B, Hkv, N, d) -> int:
+    return lib().pasa_attn_fwd_workspace_min(B, Hkv, N, d)
 
 
 def pasa_attn_fwd(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, stream=None, check=True) -> int:

@@ -114,7 +114,8 @@ namespace {
 
 // Workspace layout: the K'/V tiles, then (used by PASA_DIRECT only) one fp16 shift vector of d halfs per tile, then
 // (used by the adaptive entry point only) one 64-bit overflow counter per (batch, KV head), then (used by PASA_MIXED
-// only) one mean block of 32 x d halfs per 16 key tiles.
+// only) one mean block of 32 x d halfs per 16 key tiles, then the region of the key split: per split and query row the
+// stored output (d floats) and two doubles (sum, level).
 size_t tiles_bytes(int B, int Hkv, int N, int d)
 {
     const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
@@ -144,6 +145,39 @@ size_t kmean_offset(int B, int Hkv, int N, int d)
     return tiles_bytes(B, Hkv, N, d) + k0_bytes(B, Hkv, N, d) + group_counter_bytes(B, Hkv);
 }
 
+// Everything but the key-split region: what a call needs at least.
+size_t workspace_min_bytes(int B, int Hkv, int N, int d)
+{
+    return kmean_offset(B, Hkv, N, d) + kmean_bytes(B, Hkv, N, d);
+}
+
+// Key split.  A launch of fewer than 192 workgroups (256 query rows of one head each) leaves compute units idle; then
+// the key tiles of every workgroup are divided among up to 256 / workgroups of them, in pieces of 16 tiles, at most 16.
+constexpr int kSplitBelow = 192;
+constexpr int kMaxSplit = 16;
+constexpr size_t kSplitFloorBytes = (size_t)1 << 20;   // always there, so that short query chunks (decoding) can split
+
+int wanted_splits(int B, int Hq, int Nq, int N)
+{
+    const long units = ((long)Nq + 255) / 256 * Hq * B;
+    const int nblk16 = (int)((((long)N + kShiftTile - 1) / kShiftTile + 15) / 16);
+    if (units >= kSplitBelow || nblk16 < 2) return 1;
+    long ns = 256 / units;
+    if (ns > nblk16) ns = nblk16;
+    if (ns > kMaxSplit) ns = kMaxSplit;
+    return ns < 2 ? 1 : (int)ns;
+}
+
+size_t split_row_bytes(int d) { return (size_t)d * 4 + 16; }
+
+size_t split_region_bytes(int B, int Hq, int N, int d)
+{
+    const int ns = wanted_splits(B, Hq, N, N);
+    size_t need = ns > 1 ? (size_t)ns * (size_t)B * Hq * N * split_row_bytes(d) : 0;
+    if (need < kSplitFloorBytes) need = kSplitFloorBytes;
+    return (need + 255) / 256 * 256;
+}
+
 }  // namespace
 
 extern "C" {
@@ -151,7 +185,13 @@ extern "C" {
 size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d)
 {
     if (check_shape(B, Hq, Hkv, N, d) != PASA_OK) return 0;
-    return kmean_offset(B, Hkv, N, d) + kmean_bytes(B, Hkv, N, d);
+    return workspace_min_bytes(B, Hkv, N, d) + split_region_bytes(B, Hq, N, d);
+}
+
+size_t pasa_attn_fwd_workspace_min(int B, int Hkv, int N, int d)
+{
+    if (check_shape(B, Hkv, Hkv, N, d) != PASA_OK) return 0;
+    return workspace_min_bytes(B, Hkv, N, d);
 }
 
 }  // extern "C"
@@ -281,7 +321,7 @@ int prepare_kv_impl(const void* k, const void* v, int B, int Hkv, int N, int d, 
     st = check_shape(B, Hkv, Hkv, N, d);
     if (st != PASA_OK) return st;
     if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;   // M is a full 128 x 128 matrix
-    const size_t need = pasa_attn_fwd_workspace(B, Hkv, Hkv, N, d);
+    const size_t need = workspace_min_bytes(B, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
     const int mode = pr.variant == PASA_DIRECT ? PASA_PREP_DIRECT : pr.matrix_mode ? PASA_PREP_MATRIX : PASA_PREP_MEAN;
@@ -326,7 +366,7 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     if (st != PASA_OK) return st;
     if (Nq > kMaxN || row0 > kMaxN) return PASA_EUNSUPPORTED;
     if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
-    const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
+    const size_t need = workspace_min_bytes(B, Hkv, N, d);
     st = check_workspace(workspace, workspace_bytes, need);
     if (st != PASA_OK) return st;
     PasaLaunch p;
@@ -344,6 +384,14 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     p.nonfinite_o = pr.nonfinite_o;
     p.overflow_group = overflow_group;
     p.gate = gate;
+    // key split: as many ways as the rule wants and the bytes behind the fixed regions hold
+    int ns = (gate != nullptr || pr.variant == PASA_STRICT16) ? 1 : wanted_splits(B, Hq, Nq, N);
+    const size_t rows_all = (size_t)B * Hq * Nq, room = workspace_bytes - need;
+    while (ns > 1 && (size_t)ns * rows_all * split_row_bytes(d) > room) --ns;
+    p.nsplit = ns;
+    char* split_base = static_cast<char*>(const_cast<void*>(workspace)) + need;
+    p.part_lr = split_base;                                              // [ns][rows][2] doubles
+    p.part_o = split_base + (size_t)ns * rows_all * 16;                  // [ns][rows][d] floats
     p.stream = static_cast<hipStream_t>(stream);
     return pasa_launch_fwd(p) == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
@@ -376,7 +424,7 @@ int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o,
     st = check_shape(B, Hq, Hkv, N, d);
     if (st != PASA_OK) return st;
     if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
-    st = check_workspace(workspace, workspace_bytes, pasa_attn_fwd_workspace(B, Hq, Hkv, N, d));
+    st = check_workspace(workspace, workspace_bytes, workspace_min_bytes(B, Hkv, N, d));
     if (st != PASA_OK) return st;
     // the per-(batch, KV head) counters live behind the tiles and the shift vectors; cleared by a small kernel
     unsigned long long* group_cnt = reinterpret_cast<unsigned long long*>(
@@ -418,7 +466,7 @@ int pasa_attn_fwd_ex(const void* q, const void* k, const void* v, void* o, int B
     st = check_shape(B, Hq, Hkv, N, d);
     if (st != PASA_OK) return st;
     if (pr.matrix_mode && N % kShiftTile != 0) return PASA_EUNSUPPORTED;
-    st = check_workspace(workspace, workspace_bytes, pasa_attn_fwd_workspace(B, Hq, Hkv, N, d));
+    st = check_workspace(workspace, workspace_bytes, workspace_min_bytes(B, Hkv, N, d));
     if (st != PASA_OK) return st;
     st = pasa_prepare_kv(k, v, B, Hkv, N, d, scale, opts, workspace, workspace_bytes, stream);
     if (st != PASA_OK) return st;
@@ -490,8 +538,9 @@ extern "C" int pasa_attn_fwd_static(const void* q, const void* k, const void* v,
 {
     const int st = check_shape(B, Hq, Hkv, N, d);
     if (st != PASA_OK) return st;
-    // sizes beyond the fixed array are refused before anything else is looked at
-    const size_t need = pasa_attn_fwd_workspace(B, Hq, Hkv, N, d);
+    // sizes beyond the fixed array are refused before anything else is looked at; what the fixed regions leave of the
+    // array serves the key split
+    const size_t need = workspace_min_bytes(B, Hkv, N, d);
     if (need == 0 || need > (size_t)PASA_STATIC_WORKSPACE_BYTES) return PASA_EWORKSPACE;
     void* ws = nullptr;
     const int sp = static_scratch(&ws);

@@ -27,6 +27,11 @@ struct PasaLaunch {
     unsigned long long* overflow_group;   // non-null: the overflow count is also added to entry b * Hkv + hk of this array
     const unsigned long long* gate;   // non-null: one device counter per (batch, KV head); a workgroup does nothing
                                       // unless the counter of its own (batch, KV head) is non-zero
+    int nsplit;       // > 1: the key tiles of every (query tile, head) are swept by nsplit workgroups, whose per-row states
+                      // go to part_o ([nsplit, B*Hq*Nq, d] floats) and part_lr ([nsplit, B*Hq*Nq, 2] doubles: sum, level)
+                      // and are merged by a second kernel; ignored by PASA_K_STRICT16
+    void* part_o;
+    void* part_lr;
     hipStream_t stream;
 };
 

@@ -394,7 +394,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
               int nqt, float inva, float scale,
               int io_bf16,
               unsigned long long* ovf_s, unsigned long long* nonfinite_o, unsigned long long* ovf_group,
-              const unsigned long long* gate)
+              const unsigned long long* gate, int nsplit, float* __restrict__ part_o, double* __restrict__ part_lr)
 {
 
     constexpr int KS = D / 16;   // k-steps of S'^T = K' Q^T
@@ -425,9 +425,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // tiles (the last ones when causal) first -- which keeps the tail of the launch short; (2) the query heads that
     // share one KV head run on the same XCD(s), so that K'/V tiles are fetched into as few L2s as possible.
     // A "group" is the set of Hq/Hkv query heads of one (batch, KV head).
-    const int wg = blockIdx.x;
+    // Key split (nsplit > 1, for launches with too few workgroups to fill the chip): nsplit workgroups share one
+    // (query tile, head); each sweeps a contiguous range of key tiles and leaves its per-row state (stored output, sum,
+    // level) in part_o / part_lr for pasa_merge_splits.
+    const int split = blockIdx.x % nsplit;
+    const int wg = blockIdx.x / nsplit;
     const int G = Hq / Hkv;                 // query heads per group
-    const int ngroups = gridDim.x / (nqt * G);
+    const int ngroups = (gridDim.x / nsplit) / (nqt * G);
     int qt, grp_id, hin;                    // query tile, group, head within group
     if (ngroups % 8 == 0) {                 // each XCD owns ngroups/8 whole groups
         const int x = wg & 7, r = wg >> 3, per = (ngroups >> 3) * G;
@@ -467,8 +471,15 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         const int t = (row0 + r) / T + 1;
         return t < ntile ? t : ntile;
     };
-    const int J_wg = CAUSAL ? tiles_seen(last_row_wg) : ntile;
-    const int J_w = wave_valid ? (CAUSAL ? tiles_seen(last_row_w) : ntile) : 0;
+    // this workgroup's key tiles [j0, J_wg): all of the tiles its rows see, or -- split -- one range of them, cut at
+    // multiples of 16 tiles so that a range starts with a mean block of its own
+    const int J_all = CAUSAL ? tiles_seen(last_row_wg) : ntile;
+    const int per16 = (((J_all + 15) >> 4) + nsplit - 1) / nsplit;
+    const bool splitting = !STRICT && nsplit > 1;      // STRICT16 is never launched split: its fp16 state has no merge rule
+    const int j0 = splitting ? (split * per16 * 16 < J_all ? split * per16 * 16 : J_all) : 0;
+    const int J_wg = splitting ? (j0 + per16 * 16 < J_all ? j0 + per16 * 16 : J_all) : J_all;
+    int J_w = wave_valid ? (CAUSAL ? tiles_seen(last_row_w) : ntile) : 0;
+    if (J_w > J_wg) J_w = J_wg;
     const int row = qw0 + lq;
     const bool row_valid = row < Nq;       // rows past the end compute on zero queries and are never stored
     const int pos_w0 = row0 + qw0;         // position of the wave's first row
@@ -505,8 +516,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
         for (int i = 0; i < CPW; ++i) copy_1k_to_lds<0>(wsbuf, src + (wave * CPW + i) * 1024, dst + (wave * CPW + i) * 1024, lane);
     };
-    issue_k(0);
-    issue_kmean(0);
+    issue_k(j0);
+    issue_kmean(j0 >> 4);
 
     // Q fragments: B operand, lane (query lq, half lh) holds channels 16*ks + 8*lh .. +7
     h8 Qf[KS];
@@ -593,7 +604,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     drain_copies();
     __syncthreads();                       // barrier 0: K'(0) is in LDS
     if (grp == 1) {
-        issue_slot(0);
+        issue_slot(2 * j0);
         __syncthreads();                   // barrier 1: group B idles through slot 0
     }
 
@@ -663,14 +674,14 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         }
     };
 
-    for (int j = 0; j <= J_wg; ++j) {
+    for (int j = j0; j <= J_wg; ++j) {
         // =========================== matrix part M(j) ===========================
-        const bool do_g2 = (j >= 1 && j - 1 < J_w), do_g1 = (j < J_w);
+        const bool do_g2 = (j > j0 && j - 1 < J_w), do_g1 = (j < J_w);
         const bool tail = (tail_keys != 0) && (j == ntile - 1); // ragged last tile: padding keys are masked
         const bool diag = (CAUSAL && (j * T + T - 1 > pos_w0)) || tail;   // tile j needs the mask for this wave
         __builtin_amdgcn_s_setprio(1);
         // ---- pseudo-averages of the next 16 tiles: rows of A are the high and low parts of the tiles' mean keys ----
-        if (MSBAR && (j & 15) == 0 && do_g1) {
+        if (MSBAR && ((j & 15) == 0 || j == j0) && do_g1) {
             const _Float16* lds_km = reinterpret_cast<const _Float16*>(smem + 4 * KT_BYTES);
             f16v acc = (f16v)0.f;
 #pragma unroll
@@ -702,7 +713,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
         // =========================== vector part V(j) ===========================
         if (j < J_w) {
-            const bool first = (j == 0);
+            const bool first = (j == j0);
             if (STRICT && do_g2) fold16(j - 1);      // O <- fp16(e^{dm_j} PV) + fp16(e^{dm_{j-1}} O) for the product of tile j-1
             // ---- S' as stored: fp32, or rounded to fp16 ----
             // STRICT16 keeps the rounded scores packed two per register and works on them with packed fp16
@@ -821,7 +832,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 // the exponentials and without branches (the first tile and rows that see nothing of the tile select
                 // their values at the end) so that the latency of this chain is hidden.  The factors of the output
                 // combination go to ep_s / ec_s (the pending product of tile j-1 has been folded in above).
-                const _Float16 jm1 = (_Float16)(float)j, jn = (_Float16)(float)(j + 1);
+                const _Float16 jm1 = (_Float16)(float)(j - j0), jn = (_Float16)(float)(j - j0 + 1);
                 const _Float16 Fo = (_Float16)F, sb = (_Float16)sbar, mo = (_Float16)m, mxh = (_Float16)mx;
                 const _Float16 iv = (_Float16)inva;
                 const _Float16 Fn = (_Float16)((_Float16)((_Float16)(jm1 * Fo) + sb) / jn);
@@ -855,7 +866,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 // the end) so that it stays in one block with the exponentials.
                 // F is only a reference level (it cancels between the two correction terms), so Eq. (15)'s division by
                 // j is a multiplication by the hardware's reciprocal of j here
-                const float jm1 = (float)j, rj = __builtin_amdgcn_rcpf((float)(j + 1));
+                const float jm1 = (float)(j - j0), rj = __builtin_amdgcn_rcpf((float)(j - j0 + 1));
                 const float Fn = (jm1 * F + sbar) * rj;
                 const float dpp = inva * (F - Fn);
                 const float dpc = inva * (sbar - Fn);
@@ -929,6 +940,36 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     }
     if (grp == 0) __syncthreads();         // group B's last barrier
 
+    // ---------------- key split: leave the row state for the merge ----------------
+    if (!STRICT && part_o != nullptr) {
+        if (wave_valid) {
+            const size_t rows_all = (size_t)(gridDim.x / nsplit) / nqt * Nq;                     // B * Hq * Nq
+            const size_t grow = (size_t)(b * Hq + hq) * Nq + row;                                // global row index
+            // level of the stored output: running maximum in its frame, the frame's offset, the stored scale (exact in fp64)
+            const bool none = !(J_w > j0) || !(l > 0.f);
+            if (row_valid && lh == 0) {
+                part_lr[((size_t)split * rows_all + grow) * 2] = none ? 0.0 : (double)l;
+                part_lr[((size_t)split * rows_all + grow) * 2 + 1] =
+                    none ? -__builtin_inf() : (double)m + (double)inva * (double)F + (double)Lc;
+            }
+            float* pbase = part_o + ((size_t)split * rows_all + grow) * D;
+            if (row_valid && !none) {
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        float4 v4 = {O[cb][4 * gq], O[cb][4 * gq + 1], O[cb][4 * gq + 2], O[cb][4 * gq + 3]};
+                        *reinterpret_cast<float4*>(pbase + 32 * cb + 8 * gq + 4 * lh) = v4;
+                    }
+            }
+        }
+        if (INSTR) {
+            if (ovf_s != nullptr && n_ovf) atomicAdd(ovf_s, n_ovf);
+            if (ovf_group != nullptr && n_ovf) atomicAdd(ovf_group + grp_id, n_ovf);
+        }
+        return;
+    }
+
     // ---------------- final normalisation and store ----------------
     unsigned long long n_bad = 0;
     if (wave_valid) {
@@ -969,13 +1010,60 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     }
 }
 
+// Merge of the key splits of one call: per query row, the splits' stored outputs and sums are brought to the highest of
+// their levels (the log-sum-exp rule on R = m + Inva * F + Lc, the absolute level a split's stored output refers to)
+// and added; then Algorithm 1's final quotient.  One thread per 8 channels of a row.
+template <int D>
+__global__ __launch_bounds__(256) void pasa_merge_splits(const float* __restrict__ part_o, const double* __restrict__ part_lr,
+                                                         _Float16* __restrict__ o, size_t rows_all, int nsplit, int io_bf16,
+                                                         unsigned long long* nonfinite_o)
+{
+    constexpr int TPR = D / 8;                       // threads per row
+    const size_t grow = (size_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    if (grow >= rows_all) return;
+    const int c0 = (threadIdx.x % TPR) * 8;
+    double rmax = -__builtin_inf();
+    for (int s = 0; s < nsplit; ++s) {
+        const double r = part_lr[((size_t)s * rows_all + grow) * 2 + 1];
+        rmax = r > rmax ? r : rmax;
+    }
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float lsum = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const double r = part_lr[((size_t)s * rows_all + grow) * 2 + 1];
+        if (!(r > -__builtin_inf())) continue;       // this split saw none of the row's keys (its output is not written)
+        const float wgt = __builtin_amdgcn_exp2f((float)(r - rmax) * LOG2E);
+        lsum += wgt * (float)part_lr[((size_t)s * rows_all + grow) * 2];
+        const float4* src = reinterpret_cast<const float4*>(part_o + ((size_t)s * rows_all + grow) * D + c0);
+        const float4 a = src[0], b4 = src[1];
+        acc[0] += wgt * a.x; acc[1] += wgt * a.y; acc[2] += wgt * a.z; acc[3] += wgt * a.w;
+        acc[4] += wgt * b4.x; acc[5] += wgt * b4.y; acc[6] += wgt * b4.z; acc[7] += wgt * b4.w;
+    }
+    const float inv = 1.0f / lsum;
+    h8 out;
+    u16x8 outb;
+    unsigned n_bad = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v32 = acc[e] * inv;
+        out[e] = (_Float16)v32;
+        outb[e] = f32_to_bf16_rn(v32);
+        const float fv = io_bf16 ? __uint_as_float((unsigned)outb[e] << 16) : (float)out[e];
+        n_bad += (fv != fv || __builtin_fabsf(fv) == __builtin_inff()) ? 1u : 0u;
+    }
+    if (io_bf16) *reinterpret_cast<u16x8*>(o + grow * D + c0) = outb;
+    else *reinterpret_cast<h8*>(o + grow * D + c0) = out;
+    if (nonfinite_o != nullptr && n_bad) atomicAdd(nonfinite_o, (unsigned long long)n_bad);
+}
+
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 hipError_t launch_fwd(const PasaLaunch& p)
 {
     constexpr int RWG = 256;
     constexpr int LDS_BYTES = 4 * (T * D * 2) + (VAR == PASA_K_DIRECT ? 512 : 0) + (VAR == PASA_K_MIXED ? 64 * D + 8 * 2048 : 0);
     const int nqt = (p.Nq + RWG - 1) / RWG;
-    const dim3 grid((unsigned)(nqt * p.Hq * p.B));
+    const int nsplit = (VAR == PASA_K_STRICT16 || p.nsplit < 1) ? 1 : p.nsplit;   // fp16 state has no merge rule
+    const dim3 grid((unsigned)(nqt * p.Hq * p.B * nsplit));
     auto kern = pasa_fwd<D, VAR, CAUSAL, INSTR>;
     // the dynamic LDS limit of this instantiation is raised once per device, not on every launch
     static std::atomic<unsigned long long> lds_limit_set{0ull};
@@ -990,7 +1078,15 @@ hipError_t launch_fwd(const PasaLaunch& p)
     }
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
                        (_Float16*)p.o, (const _Float16*)p.k0, (const _Float16*)p.kmean, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
-                       p.nonfinite_o, p.overflow_group, p.gate);
+                       nsplit > 1 ? nullptr : p.nonfinite_o, p.overflow_group, p.gate, nsplit,
+                       nsplit > 1 ? (float*)p.part_o : nullptr, nsplit > 1 ? (double*)p.part_lr : nullptr);
+    e = hipGetLastError();
+    if (e != hipSuccess || nsplit == 1) return e;
+    const size_t rows_all = (size_t)p.B * p.Hq * p.Nq;
+    constexpr int RPB = 256 / (D / 8);                          // rows per block of the merge
+    hipLaunchKernelGGL(pasa_merge_splits<D>, dim3((unsigned)((rows_all + RPB - 1) / RPB)), dim3(256), 0, p.stream,
+                       (const float*)p.part_o, (const double*)p.part_lr, (_Float16*)p.o, rows_all, nsplit, p.io_bf16,
+                       p.nonfinite_o);
     return hipGetLastError();
 }
 

@@ -23,7 +23,8 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     L = P.lib()
     names = _declared_functions()
-    assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_static", "pasa_attn_fwd_workspace", "pasa_prepare_kv",
+    assert {"pasa_attn_fwd", "pasa_attn_fwd_ex", "pasa_attn_fwd_static", "pasa_attn_fwd_workspace",
+            "pasa_attn_fwd_workspace_min", "pasa_prepare_kv",
             "pasa_attn_fwd_prepared", "pasa_attn_fwd_chunk", "pasa_attn_fwd_adaptive", "pasa_shift_keys", "pasa_shift_keys_matrix", "pasa_shift_keys_direct",
             "pasa_optimal_beta", "pasa_invariance_rounded",
             "pasa_status_string", "pasa_version"} <= set(names)
@@ -36,9 +37,9 @@ def test_static_entry_point_checks_sizes_on_the_host():
     # shape errors and sizes beyond the library's fixed workspace are refused before any device is touched
     assert P.pasa_attn_fwd_static(16, 16, 16, 32, 1, 3, 2, 256, 64, 0, 0.125, check=False) == 1      # Hq % Hkv
     assert P.pasa_attn_fwd_static(16, 16, 16, 32, 1, 1, 1, 256, 96, 0, 0.125, check=False) == 2      # d
-    assert P.pasa_attn_fwd_workspace(14, 5, 5, 9216, 64) > P.STATIC_WORKSPACE_BYTES
+    assert P.pasa_attn_fwd_workspace_min(14, 5, 9216, 64) > P.STATIC_WORKSPACE_BYTES
     assert P.pasa_attn_fwd_static(16, 16, 16, 32, 14, 5, 5, 9216, 64, 0, 0.125, check=False) == 4
-    assert P.pasa_attn_fwd_workspace(1, 8, 8, 8192, 128) <= P.STATIC_WORKSPACE_BYTES
+    assert P.pasa_attn_fwd_workspace_min(1, 8, 8192, 128) <= P.STATIC_WORKSPACE_BYTES
     text = open(os.path.join(ROOT, "include", "pasa.h")).read()
     assert "#define PASA_STATIC_WORKSPACE_BYTES (33u << 20)" in text and P.STATIC_WORKSPACE_BYTES == 33 << 20
 
@@ -78,13 +79,19 @@ def test_optimal_beta_matches_paper_and_oracle(golden):
 
 def test_workspace_size():
     # K'/V tiles, then one fp16 shift vector per key tile (rounded up to 256 bytes), then the counters of the adaptive
-    # start (256 bytes here), then one mean block of 32 x d halfs per (KV head, 16 key tiles)
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256 + 4 * 4 * 64 * 128
+    # start (256 bytes here), then one mean block of 32 x d halfs per (KV head, 16 key tiles): the part every call needs
+    assert P.pasa_attn_fwd_workspace_min(1, 4, 8192, 128) == 4 * 4 * 8192 * 128 + 2 * 4 * 64 * 128 + 256 + 4 * 4 * 64 * 128
+    assert P.pasa_attn_fwd_workspace_min(1, 4, 8192, 96) == 0
+    assert P.pasa_attn_fwd_workspace_min(1, 4, 8190, 128) == P.pasa_attn_fwd_workspace_min(1, 4, 8192, 128)   # ragged last tile is padded
+    assert P.pasa_attn_fwd_workspace_min(1, 4, 1, 64) == 4 * 4 * 128 * 64 + 512 + 256 + 4 * 64 * 64
+    assert P.pasa_attn_fwd_workspace_min(1, 1, 128, 64) == 4 * 128 * 64 + 256 + 256 + 64 * 64
+    assert P.pasa_attn_fwd_workspace_min(1, 1, 17 * 128, 64) == 4 * 17 * 128 * 64 + 2 * 17 * 64 + 128 + 256 + 2 * 64 * 64
+    # then the region of the key split: 1 MiB where a self-attention call of these sizes fills the chip by itself ...
+    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128) == P.pasa_attn_fwd_workspace_min(1, 4, 8192, 128) + (1 << 20)
+    # ... and per split and row d floats + two doubles where it does not: 8 heads x 16 query tiles = 128 workgroups,
+    # 32 key tiles -> two ways
+    assert P.pasa_attn_fwd_workspace(1, 8, 8, 4096, 128) == P.pasa_attn_fwd_workspace_min(1, 8, 4096, 128) + 2 * 8 * 4096 * (128 * 4 + 16)
     assert P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 96) == 0
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 8190, 128) == P.pasa_attn_fwd_workspace(1, 28, 4, 8192, 128)   # ragged last tile is padded
-    assert P.pasa_attn_fwd_workspace(1, 28, 4, 1, 64) == 4 * 4 * 128 * 64 + 512 + 256 + 4 * 64 * 64
-    assert P.pasa_attn_fwd_workspace(1, 1, 1, 128, 64) == 4 * 128 * 64 + 256 + 256 + 64 * 64
-    assert P.pasa_attn_fwd_workspace(1, 1, 1, 17 * 128, 64) == 4 * 17 * 128 * 64 + 2 * 17 * 64 + 128 + 256 + 2 * 64 * 64
     assert P.pasa_attn_fwd_workspace(1, 28, 5, 8192, 128) == 0
 
 
@@ -137,8 +144,8 @@ def test_other_entry_points_reject_bad_arguments():
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 0}) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "row0": -1}) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "Nq": 262144 + 1}) == 2
-    assert P.pasa_attn_fwd_workspace(1, 4, 2, 256, 64) == 4 * 2 * 256 * 64 + 512 + 256 + 2 * 64 * 64
-    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": P.pasa_attn_fwd_workspace(1, 4, 2, 256, 64) - 1}) == 4
+    assert P.pasa_attn_fwd_workspace_min(1, 2, 256, 64) == 4 * 2 * 256 * 64 + 512 + 256 + 2 * 64 * 64
+    assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "workspace_bytes": P.pasa_attn_fwd_workspace_min(1, 2, 256, 64) - 1}) == 4
     assert P.pasa_shift_keys_direct(K, O, 0, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_shift_keys_direct(K, O, O, 1, 2, 256, 64, 0.5, 0.125, check=False) == 1
     assert P.pasa_attn_fwd_chunk(Q, O, **{**chunk, "N": 200, "shift_mode": P.SHIFT_MATRIX}) == 2

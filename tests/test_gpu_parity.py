@@ -470,6 +470,48 @@ def test_decoding_against_a_cache(Nq):
     assert compare(o2, o3)["maxabs"] <= 2e-3
 
 
+# ------------------------------------------------------------------ key split: few workgroups, many key tiles
+
+@pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.DIRECT])
+@pytest.mark.parametrize("Nq,N,causal,d", [(1, 4224, True, 128), (37, 6000, True, 128), (300, 2100, False, 64)])
+def test_key_split_against_the_oracle_and_against_one_workgroup_per_tile(Nq, N, causal, d, variant):
+    """Short query chunks against long keys launch few workgroups, so the library splits the key tiles of each among
+    several and merges the per-row states.  The merged result is held to the oracle like any other, and compared with
+    the same call made with the bare minimum of workspace, which cannot split."""
+    import torch
+    rng = np.random.default_rng(900 + Nq)
+    B, Hq, Hkv = 1, 4, 2
+    q = rng.standard_normal((B, Hq, Nq, d)).astype(np.float16)
+    k = (rng.standard_normal((B, Hkv, N, d)) + 3).astype(np.float16)
+    v = rng.standard_normal((B, Hkv, N, d)).astype(np.float16)
+    scale = f32(d ** -0.5)
+    row0 = N - Nq if causal else 0
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    full = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
+    bare = P.pasa_attn_fwd_workspace_min(B, Hkv, N, d)
+    assert full - bare >= 2 * B * Hq * Nq * (4 * d + 16)          # room for at least two splits of this chunk
+    outs = []
+    for nbytes in (full, bare):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        to = torch.full_like(tq, float("nan"))
+        P.pasa_prepare_kv(tk, tv, B, Hkv, N, d, scale, ws, nbytes, variant=variant)
+        P.pasa_attn_fwd_chunk(tq, to, B, Hq, Hkv, Nq, row0, N, d, causal, scale, ws, nbytes, variant=variant)
+        torch.cuda.synchronize()
+        outs.append(to.cpu().numpy())
+    split, whole = outs
+    assert np.isfinite(split).all()
+    if variant == P.DIRECT:
+        ref = np.stack([[po.direct_rows(q[b, h], k[b, h // 2], v[b, h // 2], scale, causal, BETA, 128, po.MIXED, row0)
+                         for h in range(Hq)] for b in range(B)])
+    else:
+        ref = _rows_ref(q, k, v, scale, causal, 0, Nq, row0, policy=ORACLE_POLICY[variant])
+    c, cw, cs = compare(split, ref), compare(whole, ref), compare(split, whole)
+    print(VARIANT_NAME[variant], Nq, N, "split vs oracle", c, "| unsplit vs oracle", cw, "| split vs unsplit", cs)
+    assert (c["maxabs"] <= 2e-3) if variant != P.S16 else (c["p999"] <= 2e-3)
+    assert cs["maxabs"] <= 2e-3
+
+
 # ------------------------------------------------------------------ direct-bias recovery (PASA_DIRECT, not the paper's step)
 
 @pytest.mark.parametrize("N,d", [(384, 128), (300, 64), (77, 128)])

@@ -66,9 +66,9 @@ def test_static_entry_point_refuses_what_does_not_fit():
     dev = torch.device("cuda:0")
     # 14 x 5 heads of 9216 keys, d = 64: 165 MiB of tiles, beyond the fixed array
     B, Hq, Hkv, N, d = 14, 5, 5, 9216, 64
-    assert P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d) > P.STATIC_WORKSPACE_BYTES
+    assert P.pasa_attn_fwd_workspace_min(B, Hkv, N, d) > P.STATIC_WORKSPACE_BYTES
     t = torch.zeros(16, dtype=torch.float16, device=dev)       # never touched: the size check comes first
     st = P.pasa_attn_fwd_static(t, t, t, t, B, Hq, Hkv, N, d, 0, 0.125, torch.cuda.current_stream(), check=False)
     assert st == 4 and "workspace" in P.pasa_status_string(st)
     # the largest size that fits: exactly 8 Mi elements of keys
-    assert P.pasa_attn_fwd_workspace(1, 8, 8, 8192, 128) <= P.STATIC_WORKSPACE_BYTES
+    assert P.pasa_attn_fwd_workspace_min(1, 8, 8192, 128) <= P.STATIC_WORKSPACE_BYTES
