@@ -62,11 +62,17 @@ typedef enum {
 typedef enum {
     PASA_SHIFT_MEAN = 0,   /* K' = fp16((K - beta * mean_tile(K)) * scale): mean by reduction in fp64, one rounding.
                               The shifting matrix is never formed, so its entries are never rounded. */
-    PASA_SHIFT_MATRIX = 1  /* Algorithm 1 as printed: K'^T = K^T M with every entry of M = I/alpha - beta J/(128 alpha),
+    PASA_SHIFT_MATRIX = 1, /* Algorithm 1 as printed: K'^T = K^T M with every entry of M = I/alpha - beta J/(128 alpha),
                               alpha = 1/scale, rounded to fp16 first (the rounding that section 2.3 and Eq. (20)-(22)
                               analyse); the product is exact (fp64) and rounded to fp16 once.  Evaluated as
                               (a - b) K + b sum_tile(K) with a, b the rounded diagonal and off-diagonal entry, which
                               is the same contraction.  Needs N % 128 == 0. */
+    PASA_SHIFT_MATRIX_MFMA = 2 /* The same product as a batched GEMM on the matrix core, the way Algorithm 1's pre-processing
+                              loop prints it: v_mfma_f32_32x32x16_f16 with K^T and the rounded M as operands, the 128
+                              products of an output accumulated in fp32, one rounding to fp16.  Differs from
+                              PASA_SHIFT_MATRIX by the fp32 accumulation only (a fraction of a per cent of the K' values
+                              land on the neighbouring fp16 value).  Needs N % 128 == 0; not combined with the adaptive
+                              entry point. */
 } pasa_shift_mode;
 
 /* Element type of q, k, v and o.  The method computes in fp16: bf16 inputs are converted to fp16 as they are loaded
@@ -185,6 +191,10 @@ int pasa_shift_keys(const void* k, void* kprime, int B, int Hkv, int N, int d,
  * alpha = 1/kscale.  N must be a multiple of 128. */
 int pasa_shift_keys_matrix(const void* k, void* kprime, int B, int Hkv, int N, int d,
                            double beta, double kscale, void* stream);
+
+/* The same contraction on the matrix core (PASA_SHIFT_MATRIX_MFMA): fp32 accumulation, one rounding to fp16. */
+int pasa_shift_keys_matrix_mfma(const void* k, void* kprime, int B, int Hkv, int N, int d,
+                                double beta, double kscale, void* stream);
 
 /* The shift of PASA_DIRECT: k0[b, h, t, :] = fp16(beta * mean of key tile t) ([B, Hkv, ceil(N/128), d], DEVICE, written)
  * and K' = fp16((K - k0) * kscale) in the plain layout. */

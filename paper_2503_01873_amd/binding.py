@@ -10,7 +10,7 @@ import ctypes
 import os
 
 MIXED, STRICT16, NAIVE16, S16, DIRECT = 0, 1, 2, 3, 4
-SHIFT_MEAN, SHIFT_MATRIX = 0, 1
+SHIFT_MEAN, SHIFT_MATRIX, SHIFT_MATRIX_MFMA = 0, 1, 2
 IO_F16, IO_BF16 = 0, 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
     L.pasa_shift_keys.restype = ci
     L.pasa_shift_keys_matrix.argtypes = [vp, vp, ci, ci, ci, ci, cd, cd, vp]
     L.pasa_shift_keys_matrix.restype = ci
+    L.pasa_shift_keys_matrix_mfma.argtypes = [vp, vp, ci, ci, ci, ci, cd, cd, vp]
+    L.pasa_shift_keys_matrix_mfma.restype = ci
     L.pasa_shift_keys_direct.argtypes = [vp, vp, vp, ci, ci, ci, ci, cd, cd, vp]
     L.pasa_shift_keys_direct.restype = ci
     L.pasa_optimal_beta.argtypes = [cd, ci, ci]
@@ -190,6 +192,12 @@ def pasa_shift_keys_matrix(k, kprime, B, Hkv, N, d, beta, kscale, stream=None, c
     st = lib().pasa_shift_keys_matrix(_ptr(k), _ptr(kprime), B, Hkv, N, d, float(beta), float(kscale),
                                       _stream(stream))
     return _check(st, "pasa_shift_keys_matrix", check)
+
+
+def pasa_shift_keys_matrix_mfma(k, kprime, B, Hkv, N, d, beta, kscale, stream=None, check=True) -> int:
+    st = lib().pasa_shift_keys_matrix_mfma(_ptr(k), _ptr(kprime), B, Hkv, N, d, float(beta), float(kscale),
+                                           _stream(stream))
+    return _check(st, "pasa_shift_keys_matrix_mfma", check)
 
 
 def pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, workspace, workspace_bytes, stream=None,

@@ -10,7 +10,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libpasa.so")
-SOURCES = ["pasa_api.hip", "pasa_kernels.hip"]
+SOURCES = ["pasa_api.hip", "pasa_kernels.hip", "pasa_shift_gemm.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950",

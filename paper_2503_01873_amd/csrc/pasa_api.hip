@@ -244,6 +244,21 @@ int pasa_shift_keys_matrix(const void* k, void* kprime, int B, int Hkv, int N, i
     return shift_keys_common(k, kprime, B, Hkv, N, d, beta, kscale, PASA_PREP_MATRIX, nullptr, stream);
 }
 
+int pasa_shift_keys_matrix_mfma(const void* k, void* kprime, int B, int Hkv, int N, int d, double beta, double kscale,
+                                void* stream)
+{
+    const int st = check_shape(B, Hkv, Hkv, N, d);
+    if (st != PASA_OK) return st;
+    if (k == nullptr || kprime == nullptr || !aligned(k, 16) || !aligned(kprime, 16) || k == kprime) return PASA_EINVAL;
+    if (!(beta >= 0.0) || !(beta < 1.0) || !isfinite(kscale) || !(kscale > 0.0)) return PASA_EINVAL;
+    if (N % kShiftTile != 0) return PASA_EUNSUPPORTED;
+    double amb, b16;
+    rounded_shift_matrix(beta, kscale, &amb, &b16);
+    const hipError_t e = pasa_launch_shift_gemm(k, nullptr, kprime, B, Hkv, N, d, amb + b16, b16, 0, nullptr,
+                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+}
+
 int pasa_shift_keys_direct(const void* k, void* kprime, void* k0, int B, int Hkv, int N, int d, double beta, double kscale,
                            void* stream)
 {
@@ -258,6 +273,7 @@ struct Params {
     double beta;      // shift fraction used by the pre-processing kernel (matrix mode: a - b)
     double kscale;    // factor folded into K' (matrix mode: b)
     int matrix_mode;  // K' by the fp16-rounded shifting matrix instead of by the tile mean
+    int mfma_shift;   // ... and that product on the matrix core (fp32 accumulation) instead of exactly
     int io_bf16;      // q, k, v, o hold bf16
     float inva;       // beta/(1-beta) rounded to the statistics precision
     unsigned long long* overflow_s;
@@ -271,14 +287,15 @@ int resolve(const pasa_opts* opts, float scale, Params* out)
     pasa_opts op = {-1.f, PASA_MIXED, kShiftTile, nullptr, nullptr, PASA_SHIFT_MEAN, PASA_IO_F16};
     if (opts != nullptr) op = *opts;
     if (op.variant < PASA_MIXED || op.variant > PASA_DIRECT) return PASA_EINVAL;
-    if (op.variant == PASA_DIRECT && op.shift_mode == PASA_SHIFT_MATRIX) return PASA_EINVAL;   // it has its own shift
-    if (op.shift_mode != PASA_SHIFT_MEAN && op.shift_mode != PASA_SHIFT_MATRIX) return PASA_EINVAL;
+    if (op.shift_mode != PASA_SHIFT_MEAN && op.shift_mode != PASA_SHIFT_MATRIX && op.shift_mode != PASA_SHIFT_MATRIX_MFMA)
+        return PASA_EINVAL;
+    if (op.variant == PASA_DIRECT && op.shift_mode != PASA_SHIFT_MEAN) return PASA_EINVAL;   // it has its own shift
     if (op.io_dtype != PASA_IO_F16 && op.io_dtype != PASA_IO_BF16) return PASA_EINVAL;
     if (op.shift_tile != 0 && op.shift_tile != kShiftTile) return PASA_EUNSUPPORTED;
     if (!(op.beta < 1.f)) return PASA_EINVAL;              // also rejects NaN
     // beta and the invariance beta/(1-beta) in fp64.  Default by mean: the invariance is exactly 63.5.  Default by
     // matrix: the paper's adopted solution of the optimal accuracy condition for fp16 and n = 128 (Table 3).
-    const double beta_default = op.shift_mode == PASA_SHIFT_MATRIX ? 0.984497 : 63.5 / 64.5;
+    const double beta_default = op.shift_mode != PASA_SHIFT_MEAN ? 0.984497 : 63.5 / 64.5;
     double beta = op.beta < 0.f ? beta_default : (double)op.beta;
     double kscale = (double)scale;
     if (op.variant == PASA_NAIVE16) {   // no shift, static scaling applied after the first GEMM (Eq. (1), (2))
@@ -290,7 +307,8 @@ int resolve(const pasa_opts* opts, float scale, Params* out)
     out->beta = beta;
     out->kscale = kscale;
     out->io_bf16 = op.io_dtype == PASA_IO_BF16;
-    out->matrix_mode = op.shift_mode == PASA_SHIFT_MATRIX;
+    out->matrix_mode = op.shift_mode != PASA_SHIFT_MEAN && op.variant != PASA_NAIVE16;
+    out->mfma_shift = out->matrix_mode && op.shift_mode == PASA_SHIFT_MATRIX_MFMA;
     if (out->matrix_mode) rounded_shift_matrix(beta, kscale, &out->beta, &out->kscale);
     out->inva = op.variant == PASA_STRICT16 ? (float)round_to_format(inva_d, 11, -14, 15) : (float)inva_d;
     out->overflow_s = op.overflow_s;
@@ -327,6 +345,15 @@ int prepare_kv_impl(const void* k, const void* v, int B, int Hkv, int N, int d, 
     const int mode = pr.variant == PASA_DIRECT ? PASA_PREP_DIRECT : pr.matrix_mode ? PASA_PREP_MATRIX : PASA_PREP_MEAN;
     void* k0out = static_cast<char*>(workspace) + tiles_bytes(B, Hkv, N, d);
     void* kmean = pr.variant == PASA_MIXED ? static_cast<char*>(workspace) + kmean_offset(B, Hkv, N, d) : nullptr;
+    if (pr.mfma_shift) {
+        // V by the re-tiling blocks of the pre-processing kernel, K' by the GEMM (pr.beta carries a - b, pr.kscale b)
+        hipError_t e2 = pasa_launch_prep(nullptr, v, workspace, nullptr, B, Hkv, N, d, 0.0, 1.0, PASA_PREP_MEAN, pr.io_bf16,
+                                         nullptr, nullptr, pr.gate, static_cast<hipStream_t>(stream));
+        if (e2 == hipSuccess)
+            e2 = pasa_launch_shift_gemm(k, workspace, nullptr, B, Hkv, N, d, pr.beta + pr.kscale, pr.kscale, pr.io_bf16,
+                                        kmean, static_cast<hipStream_t>(stream));
+        return e2 == hipSuccess ? PASA_OK : PASA_ELAUNCH;
+    }
     const hipError_t e = pasa_launch_prep(k, v, workspace, nullptr, B, Hkv, N, d, pr.beta, pr.kscale, mode, pr.io_bf16,
                                           k0out, kmean, pr.gate, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PASA_OK : PASA_ELAUNCH;
@@ -418,6 +445,7 @@ int pasa_attn_fwd_adaptive(const void* q, const void* k, const void* v, void* o,
     if (causal != 0 && causal != 1) return PASA_EINVAL;
     if (opts == nullptr || opts->overflow_s == nullptr || !aligned(opts->overflow_s, 8)) return PASA_EINVAL;
     if (opts->nonfinite_o != nullptr || opts->variant == PASA_NAIVE16) return PASA_EINVAL;
+    if (opts->shift_mode == PASA_SHIFT_MATRIX_MFMA) return PASA_EINVAL;    // the GEMM pre-pass has no per-head gate
     Params pr;
     int st = resolve(opts, scale, &pr);
     if (st != PASA_OK) return st;

@@ -43,11 +43,18 @@ struct PasaLaunch {
 // PASA_PREP_MATRIX: K' = fp16(beta * K + kscale * tile sum), i.e. the product with the fp16-rounded shifting
 //                   matrix a I + b (J - I) when beta carries a - b and kscale carries b (N % 128 == 0 only).
 // PASA_PREP_DIRECT: k0 = fp16(beta * tile mean) goes to k0out ([B, Hkv, tiles, d]) and K' = fp16((K - k0) * kscale).
+// k == nullptr: only V is re-tiled (the keys come from pasa_launch_shift_gemm).
 // kmean_out != nullptr: also the mean blocks of the rounded K' ([B, Hkv, ceil(tiles/16), 32, d] halfs) that
 // PASA_K_MIXED reads.
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
                             void* k0out, void* kmean_out, const unsigned long long* gate, hipStream_t stream);
+
+// Algorithm 1's pre-processing loop as printed: K'^T = K^T M on the matrix core, M = a on the diagonal and b elsewhere
+// (both fp16 values), fp32 accumulation, one rounding to fp16.  N % 128 == 0.  Writes the K' tiles of the workspace
+// (or, plain_out != nullptr, the plain [B,Hkv,N,d] layout) and, kmean_out != nullptr, the mean blocks of that K'.
+hipError_t pasa_launch_shift_gemm(const void* k, void* ws, void* plain_out, int B, int Hkv, int N, int d, double a16,
+                                 double b16, int in_bf16, void* kmean_out, hipStream_t stream);
 
 hipError_t pasa_launch_fwd(const PasaLaunch& p);
 

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
                                                     _Float16* __restrict__ plain_out, _Float16* __restrict__ k0out,
                                                     _Float16* __restrict__ kmean_out,
                                                     int N, int ntile, double beta, double kscale, int shift_mode,
-                                                    int in_bf16, const unsigned long long* gate)
+                                                    int in_bf16, const unsigned long long* gate, int y_off)
 {
     // adaptive start: nothing overflowed in this (batch, KV head), its shifted pass is not needed
     if (gate != nullptr && gate[blockIdx.x / ntile] == 0) return;
@@ -129,10 +129,11 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     const size_t src_off = (head * (size_t)N + (size_t)t * T) * D;
     const int tid = threadIdx.x;
 
-    if (blockIdx.y >= NS) {
+    const int by = blockIdx.y + y_off;     // y_off = NS: only the value blocks are launched
+    if (by >= NS) {
         // ---- values: keys [n0, n0 + TB) of the tile, all channels ----
         _Float16 (*vs)[D + 8] = reinterpret_cast<_Float16 (*)[D + 8]>(lds_raw);   // +8 halfs: rows 16 bytes apart in bank space
-        const int n0 = (blockIdx.y - NS) * TB;
+        const int n0 = (by - NS) * TB;
         const _Float16* vsrc = v + src_off;
         constexpr int VCH = D / 8;
         for (int idx = tid; idx < TB * VCH; idx += 256) {
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
     double (*psum)[DB] = reinterpret_cast<double (*)[DB]>(lds_raw);              // [KL] partial column sums
     double (*psum2)[DB] = psum + KL;                                             // [PARTS] second stage
     double* colv = reinterpret_cast<double*>(psum2 + PARTS);                     // [DB] mean (or sum, or k0) per channel
-    const int cg = blockIdx.y;
+    const int cg = by;
     const int c8 = tid % CH, kl = tid / CH;
     const int ch0 = cg * DB + 8 * c8;                    // first of this thread's 8 channels
     const _Float16* ksrc = k + src_off;
@@ -1118,13 +1119,14 @@ hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_
                             void* k0out, void* kmean_out, const unsigned long long* gate, hipStream_t stream)
 {
     const int ntile = (N + T - 1) / T;
-    const dim3 grid((unsigned)((size_t)B * Hkv * ntile), (v != nullptr ? 2u : 1u) * PASA_PREP_SPLIT);   // y: key channel groups, then value key groups
+    const int y_off = k == nullptr ? PASA_PREP_SPLIT : 0;     // no keys given: the value blocks alone
+    const dim3 grid((unsigned)((size_t)B * Hkv * ntile), (v != nullptr && k != nullptr ? 2u : 1u) * PASA_PREP_SPLIT);   // y: key channel groups, then value key groups
     if (d == 128)
         hipLaunchKernelGGL(pasa_prep_kv<128>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, (_Float16*)kmean_out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, (_Float16*)kmean_out, N, ntile, beta, kscale, shift_mode, in_bf16, gate, y_off);
     else
         hipLaunchKernelGGL(pasa_prep_kv<64>, grid, dim3(256), 0, stream, (const _Float16*)k, (const _Float16*)v,
-                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, (_Float16*)kmean_out, N, ntile, beta, kscale, shift_mode, in_bf16, gate);
+                           (_Float16*)ws, (_Float16*)plain_out, (_Float16*)k0out, (_Float16*)kmean_out, N, ntile, beta, kscale, shift_mode, in_bf16, gate, y_off);
     return hipGetLastError();
 }
 

@@ -120,7 +120,8 @@ def _ex(**over):
     (dict(causal=2), 1), (dict(variant=5), 1), (dict(variant=-1), 1), (dict(variant=P.DIRECT, shift_mode=P.SHIFT_MATRIX), 1), (dict(beta=1.0), 1), (dict(beta=float("nan")), 1),
     (dict(d=96), 2), (dict(d=256), 2), (dict(N=262144 + 128), 2), (dict(shift_tile=64), 2),
     (dict(ws=0), 4), (dict(ws=WS + 16), 4), (dict(wsb=1024), 4),
-    (dict(shift_mode=2), 1), (dict(shift_mode=-1), 1), (dict(shift_mode=P.SHIFT_MATRIX, N=200), 2),
+    (dict(shift_mode=3), 1), (dict(shift_mode=-1), 1), (dict(shift_mode=P.SHIFT_MATRIX, N=200), 2),
+    (dict(shift_mode=P.SHIFT_MATRIX_MFMA, N=200), 2), (dict(variant=P.DIRECT, shift_mode=P.SHIFT_MATRIX_MFMA), 1),
     (dict(io_dtype=2), 1), (dict(io_dtype=-1), 1),
 ])
 def test_attn_fwd_ex_rejects_bad_arguments(over, want):

@@ -302,6 +302,51 @@ def test_shift_keys_matrix_bit_exact(d, beta, kscale):
         assert (got != mean_form).mean() > 0.05
 
 
+@pytest.mark.parametrize("d,beta,kscale", [(128, PAPER_BETA, 128 ** -0.5), (64, PAPER_BETA, 0.125), (128, 0.9375, 1.0)])
+def test_shift_keys_matrix_on_the_matrix_core_within_fp32_accumulation(d, beta, kscale):
+    """The pre-processing GEMM of Algorithm 1 on the matrix core: same operands as the exact evaluation (K and the
+    fp16-rounded M), but the 128 products of an output are accumulated in fp32.  Bound on the accumulated value:
+    |fl32 sum - exact| <= 128 * 2^-24 * sum_p |M[p,q] K[p,c]| (one rounding per addition, first order); the stored fp16
+    value is then within half an fp16 step (2^-11 relative, or 2^-25 absolute in the subnormal range) of that."""
+    import torch
+    rng = np.random.default_rng(1500 + d)
+    k = (rng.standard_normal((2, 3, 384, d)) * rng.uniform(0.1, 30, (1, 1, 1, d)) + rng.uniform(-80, 80, (2, 3, 1, d))).astype(np.float16)
+    tk = torch.from_numpy(k).cuda()
+    out = torch.empty_like(tk)
+    P.pasa_shift_keys_matrix_mfma(tk, out, 2, 3, 384, d, beta, kscale)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    M16 = po.fl(po.shift_matrix(beta, 128, 1.0 / kscale), "f16")
+    K64 = k.astype(np.float64).reshape(2, 3, 3, 128, d)
+    exact = np.einsum("pq,bhjpc->bhjqc", M16, K64).reshape(2, 3, 384, d)
+    mag = np.einsum("pq,bhjpc->bhjqc", np.abs(M16), np.abs(K64)).reshape(2, 3, 384, d)
+    bound = 128 * 2.0 ** -24 * mag + np.maximum(2.0 ** -11 * np.abs(exact), 2.0 ** -25) * 1.0001
+    assert (np.abs(got - exact) <= bound).all()
+    want = np.stack([[po.shift_keys(k[b, h], beta, kscale, 128, "gemm_m") for h in range(3)] for b in range(2)])
+    frac = float((out.cpu().numpy() != want).mean())
+    print("K' values that differ from the exactly accumulated product: %.4f" % frac)
+    assert frac <= 0.02
+
+
+@pytest.mark.parametrize("idx,N,over", [(1, 256, {}), (3, 640, dict(Hq=7, Hkv=1))])
+def test_matrix_shift_on_the_matrix_core_end_to_end(idx, N, over):
+    w = _small(idx, N, **over)
+    q, k, v = gen_full(w)
+    scale = f32(w.scale)
+    o, cnt = gpu_attn(q, k, v, w.causal, scale, P.MIXED, counters=True, shift_mode=P.SHIFT_MATRIX_MFMA)
+    o_exact, _ = gpu_attn(q, k, v, w.causal, scale, P.MIXED, shift_mode=P.SHIFT_MATRIX)
+    ref = po.pasa_bhnd(q, k, v, scale, w.causal, PAPER_BETA, 128, po.MIXED, shift="gemm_m")
+    gold = po.attention_fp64_bhnd(q, k, v, scale, w.causal)
+    c, ce = compare(o, ref), compare(o, o_exact)
+    r_gpu, r_or = po.rmse(o, gold), po.rmse(ref, gold)
+    print(w.name, "vs oracle", c, "vs exactly accumulated shift", ce, "rmse gpu %.3e oracle %.3e" % (r_gpu, r_or))
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    # a K' value that lands on the neighbouring fp16 value moves one score by 2^-11 |q_c K'_c| and the tile's
+    # pseudo-average by 1/128 of that, times the invariance: far inside the tolerance of the exact path
+    assert c["p999"] <= 2e-3 and c["maxabs"] <= 4e-3
+    assert abs(r_gpu - r_or) <= 0.05 * r_or + 2e-5
+
+
 @pytest.mark.parametrize("variant", [P.MIXED, P.S16, P.STRICT16])
 def test_matrix_shift_tiny_workload_full_tensor(variant):
     w = workload(1)
