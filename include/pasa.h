@@ -54,8 +54,8 @@ typedef enum {
                           vector k0 = fp16(beta * mean_tile(K)), K' = fp16((K - k0) * scale), and the removed bias is
                           added back as scale * (q . k0) (legal by Eq. (9): any shift leaves softmax unchanged)
                           followed by ordinary online softmax (Eq. (4)-(8)).  There is no pseudo-average Sbar' and no
-                          factor beta/(1-beta), so the rounding noise of K' is not amplified; costs eight more MFMAs per
-                          tile.  PASA_SHIFT_MATRIX does not apply to it. */
+                          factor beta/(1-beta), so the rounding noise of K' is not amplified.  The other shift modes do
+                          not apply to it. */
 } pasa_variant;
 
 /* How the key pre-processing loop of Algorithm 1 forms K' (Eq. (10), (11)). */
@@ -101,11 +101,11 @@ int pasa_attn_fwd(const void* q, const void* k, const void* v, void* o,
 
 /* Bytes of device workspace pasa_attn_fwd_ex needs for these sizes: shifted keys K' and re-tiled values, both fp16
  * (4*B*Hkv*ceil(N/128)*128*d bytes), then one fp16 shift vector per key tile (2*B*Hkv*ceil(N/128)*d bytes, rounded up
- * to a multiple of 256; written and read by PASA_DIRECT only), then one 64-bit counter per (batch, KV head) (8*B*Hkv
+ * to a multiple of 256; written by PASA_DIRECT's pre-processing, in plain order), then one 64-bit counter per (batch, KV head) (8*B*Hkv
  * bytes, rounded up to a multiple of 256; used by pasa_attn_fwd_adaptive only), then for every (batch, KV head) and
  * group of 16 key tiles the per-channel means of the rounded K' of those tiles as fp16 pairs (64*d bytes per group,
- * B*Hkv*ceil(ceil(N/128)/16) groups; written and read by PASA_MIXED only, which takes the pseudo-average of Eq. (14)
- * as the query times that mean, Eq. (12)); these regions together are pasa_attn_fwd_workspace_min().  Last comes the
+ * B*Hkv*ceil(ceil(N/128)/16) groups; PASA_MIXED takes the pseudo-average of Eq. (14) as the query times that mean,
+ * Eq. (12); for PASA_DIRECT the same blocks hold the tiles' shift vectors k0 instead); these regions together are pasa_attn_fwd_workspace_min().  Last comes the
  * region of the key split: when a call would launch fewer than 192 workgroups (one per 256 query rows of a head) on the
  * 256 compute units, the key tiles of every workgroup are divided among up to 16 workgroups in pieces of 16 tiles,
  * each leaves per query row its unnormalised output (d floats) and two doubles (running sum, level), and a second

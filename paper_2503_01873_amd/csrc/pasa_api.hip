@@ -344,7 +344,8 @@ int prepare_kv_impl(const void* k, const void* v, int B, int Hkv, int N, int d, 
     if (st != PASA_OK) return st;
     const int mode = pr.variant == PASA_DIRECT ? PASA_PREP_DIRECT : pr.matrix_mode ? PASA_PREP_MATRIX : PASA_PREP_MEAN;
     void* k0out = static_cast<char*>(workspace) + tiles_bytes(B, Hkv, N, d);
-    void* kmean = pr.variant == PASA_MIXED ? static_cast<char*>(workspace) + kmean_offset(B, Hkv, N, d) : nullptr;
+    void* kmean = (pr.variant == PASA_MIXED || pr.variant == PASA_DIRECT)
+                      ? static_cast<char*>(workspace) + kmean_offset(B, Hkv, N, d) : nullptr;
     if (pr.mfma_shift) {
         // V by the re-tiling blocks of the pre-processing kernel, K' by the GEMM (pr.beta carries a - b, pr.kscale b)
         hipError_t e2 = pasa_launch_prep(nullptr, v, workspace, nullptr, B, Hkv, N, d, 0.0, 1.0, PASA_PREP_MEAN, pr.io_bf16,
@@ -398,7 +399,6 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     if (st != PASA_OK) return st;
     PasaLaunch p;
     p.q = q; p.ws = workspace; p.o = o;
-    p.k0 = static_cast<const char*>(workspace) + tiles_bytes(B, Hkv, N, d);
     p.kmean = static_cast<const char*>(workspace) + kmean_offset(B, Hkv, N, d);
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.N = N; p.d = d;
     p.Nq = Nq; p.row0 = causal ? row0 : 0;

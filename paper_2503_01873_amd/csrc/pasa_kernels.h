@@ -13,8 +13,8 @@ struct PasaLaunch {
     const void* q;
     const void* ws;   // per (batch, KV head, key tile): shifted-key tile then value tile, fragment-major layout
     void* o;
-    const void* k0;   // PASA_K_DIRECT: per (batch, KV head, key tile) the fp16 shift vector, d halfs each
-    const void* kmean;  // PASA_K_MIXED: per (batch, KV head, 16 key tiles) the mean block, 32 x d halfs
+    const void* kmean;  // PASA_K_MIXED: per (batch, KV head, 16 key tiles) the mean block, 32 x d halfs;
+                        // PASA_K_DIRECT: the same blocks holding the tiles' shift vectors k0
     int B, Hq, Hkv, N, d;   // N: keys
     int Nq, row0;           // query rows given, and the sequence position of the first of them
     int causal;
@@ -45,7 +45,7 @@ struct PasaLaunch {
 // PASA_PREP_DIRECT: k0 = fp16(beta * tile mean) goes to k0out ([B, Hkv, tiles, d]) and K' = fp16((K - k0) * kscale).
 // k == nullptr: only V is re-tiled (the keys come from pasa_launch_shift_gemm).
 // kmean_out != nullptr: also the mean blocks of the rounded K' ([B, Hkv, ceil(tiles/16), 32, d] halfs) that
-// PASA_K_MIXED reads.
+// PASA_K_MIXED reads; with PASA_PREP_DIRECT the blocks hold the shift vectors k0 instead (what PASA_K_DIRECT reads).
 hipError_t pasa_launch_prep(const void* k, const void* v, void* ws, void* plain_out,
                             int B, int Hkv, int N, int d, double beta, double kscale, int shift_mode, int in_bf16,
                             void* k0out, void* kmean_out, const unsigned long long* gate, hipStream_t stream);

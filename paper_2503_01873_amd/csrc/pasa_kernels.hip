@@ -97,6 +97,26 @@ __device__ inline _Float16 double_to_half_rn(double x)
 #ifndef PASA_PREP_SPLIT
 #define PASA_PREP_SPLIT 4
 #endif
+
+// One channel c of the two rows that key tile t owns in its "mean block" (a 32-row x D A operand per 16 tiles, in the
+// K' tile's chunk order: chunk (c/8)*32 + row holds channels 8*(c/8)..+7 of row `row`).  Tile t of the group has its
+// "high" row at 8*(t/4) + t%4 and its "low" row four rows further down: in the 32x32 accumulator layout the first kind
+// of row lands in lanes 0-31 and the second in lanes 32-63 of the same accumulator register.  The last tile of a head
+// also clears the rows of the tiles that do not exist.
+__device__ inline void write_block_rows(_Float16* blocks, size_t head, int ntile, int t, int c, int D, _Float16 hi, _Float16 lo)
+{
+    const int nblk = (ntile + 15) / 16;
+    const int t16 = t & 15, row = 8 * (t16 >> 2) + (t16 & 3);
+    _Float16* blk = blocks + ((head * (size_t)nblk + (size_t)(t >> 4)) * 32) * D;
+    blk[((size_t)(c / 8) * 32 + row) * 8 + (c % 8)] = hi;
+    blk[((size_t)(c / 8) * 32 + row + 4) * 8 + (c % 8)] = lo;
+    if (t == ntile - 1)
+        for (int u = t16 + 1; u < 16; ++u) {
+            const int ru = 8 * (u >> 2) + (u & 3);
+            blk[((size_t)(c / 8) * 32 + ru) * 8 + (c % 8)] = (_Float16)0;
+            blk[((size_t)(c / 8) * 32 + ru + 4) * 8 + (c % 8)] = (_Float16)0;
+        }
+}
 // ---------------------------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__ k, const _Float16* __restrict__ v,
@@ -195,6 +215,8 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
             const _Float16 k0h = double_to_half_rn(__dmul_rn(beta, val));
             val = (double)k0h;
             k0out[tile * (size_t)D + cg * DB + tid] = k0h;
+            // the main kernel reads the vector from the tile's "high" row of a mean block (below); the "low" row is zero
+            if (kmean_out != nullptr) write_block_rows(kmean_out, head, ntile, t, cg * DB + tid, D, k0h, (_Float16)0);
         }
         colv[tid] = val;
     }
@@ -232,13 +254,9 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
             *reinterpret_cast<h8*>(wsout + tile * (size_t)(2 * T * D) + ((size_t)(ch0 / 8) * T + n) * 8) = out;
         }
     }
-    if (kmean_out == nullptr) return;
+    if (kmean_out == nullptr || shift_mode == PASA_PREP_DIRECT) return;
 
     // ---- mean block: column sum of the rounded K' / 128 (an exact scaling), as an fp16 pair hi + lo ----
-    // A block serves 16 consecutive key tiles and is a 32-row x D A operand in the K' tile's chunk order (chunk
-    // (c/8)*32 + row holds channels 8*(c/8)..+7 of row `row`).  Tile t of the group has its high part in row
-    // 8*(t/4) + t%4 and its low part four rows further down: in the 32x32 accumulator layout the first kind of row
-    // lands in lanes 0-31 and the second in lanes 32-63 of the same accumulator register.
     __syncthreads();                       // psum is reused
 #pragma unroll
     for (int e = 0; e < 8; ++e) psum[kl][8 * c8 + e] = rs[e];
@@ -259,17 +277,7 @@ __global__ __launch_bounds__(256) void pasa_prep_kv(const _Float16* __restrict__
         // subnormal for every mean below 0.125, and the matrix core reads those as zero
         const _Float16 hi = double_to_half_rn(m128);
         const _Float16 lo = double_to_half_rn((m128 - (double)hi) * 2048.0);
-        const int nblk = (ntile + 15) / 16;
-        const int t16 = t & 15, row = 8 * (t16 >> 2) + (t16 & 3), c = cg * DB + tid;
-        _Float16* blk = kmean_out + ((head * (size_t)nblk + (size_t)(t >> 4)) * 32) * D;
-        blk[((size_t)(c / 8) * 32 + row) * 8 + (c % 8)] = hi;
-        blk[((size_t)(c / 8) * 32 + row + 4) * 8 + (c % 8)] = lo;
-        if (t == ntile - 1)                                   // rows of the tiles that do not exist: zeros
-            for (int u = t16 + 1; u < 16; ++u) {
-                const int ru = 8 * (u >> 2) + (u & 3);
-                blk[((size_t)(c / 8) * 32 + ru) * 8 + (c % 8)] = (_Float16)0;
-                blk[((size_t)(c / 8) * 32 + ru + 4) * 8 + (c % 8)] = (_Float16)0;
-            }
+        write_block_rows(kmean_out, head, ntile, t, cg * DB + tid, D, hi, lo);
     }
 }
 
@@ -326,9 +334,9 @@ __device__ inline float add_pair(h2 v, float acc)
 // (acc + a) + b, the same sum with two v_fma_mix_f32 (half * 1.0 + acc, the half read straight from its packed
 // register).  v_dot2_f32_f16 takes its turn in the matrix pipeline: beside a wave that issues MFMAs back to back it
 // holds its own wave for 24 cycles (a v_fma_mix_f32: 7) while costing the shared issue port little.  Where the vector
-// part alone is the critical path (STRICT16) two of these are faster than one of those; where both wave groups keep
-// the issue port busy (the fp32 variants) they are slower.  (The compiler folds fma(x, 1, acc) to an add with two
-// separate conversions, hence the asm.)
+// part is short enough for that wait to show (STRICT16; MIXED since its pseudo-average moved to the matrix core) two of
+// these are faster than one of those; in the other variants they are slower.  (The compiler folds fma(x, 1, acc) to
+// an add with two separate conversions, hence the asm.)
 __device__ inline float add_pair_mix(h2 v, float acc)
 {
     asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]" : "+v"(acc) : "v"(v));
@@ -391,7 +399,7 @@ __device__ inline void copy_1k_to_lds(__amdgpu_buffer_rsrc_t src, int soff, char
 template <int D, int VAR, bool CAUSAL, bool INSTR>
 __global__ __launch_bounds__(512, 2)
 void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Float16* __restrict__ o,
-              const _Float16* __restrict__ k0, const _Float16* __restrict__ kmean, int Hq, int Hkv, int Nq, int row0, int N,
+              const _Float16* __restrict__ kmean, int Hq, int Hkv, int Nq, int row0, int N,
               int nqt, float inva, float scale,
               int io_bf16,
               unsigned long long* ovf_s, unsigned long long* nonfinite_o, unsigned long long* ovf_group,
@@ -406,7 +414,8 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     constexpr bool DIRECT = (VAR == PASA_K_DIRECT);               // bias added back as scale * (q . k0), no pseudo-average
     // MIXED takes the pseudo-average as q . colmean(K') (Eq. (12), (14)) on the matrix core, 16 tiles at a time,
     // instead of summing 128 scores per row and tile on the vector unit
-    constexpr bool MSBAR = (VAR == PASA_K_MIXED);
+    // DIRECT takes q . k0 of the tiles the same way (their "mean block" holds the shift vectors, low rows zero)
+    constexpr bool MSBAR = (VAR == PASA_K_MIXED || VAR == PASA_K_DIRECT);
     constexpr int KM_BYTES = 64 * D;                            // one mean block: 32 rows x D halfs
     constexpr int SB_OFF = 4 * (T * D * 2) + KM_BYTES;          // per-wave [16 tiles][32 rows] floats behind it
     constexpr int KT_BYTES = T * D * 2;                         // one K' (or V) tile
@@ -491,16 +500,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     const __amdgpu_buffer_rsrc_t wsbuf =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wsbase), 0, ntile * TILE_BYTES, 0x00020000);
 
-    // DIRECT: the shift vectors k0 of this head's tiles (D halfs each); a tile's vector goes to one of two 256-byte LDS
-    // slots behind the tile buffers with one wave-wide 4-byte-per-lane copy (for D = 64 its upper half is padding)
-    const __amdgpu_buffer_rsrc_t k0buf = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<_Float16*>(DIRECT ? k0 + ((size_t)(b * Hkv + hk) * ntile) * D : q), 0, DIRECT ? ntile * D * 2 : 0,
-        0x00020000);
-    auto issue_k0 = [&](int j) {
-        if (DIRECT && wave == 0)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(k0buf, (__attribute__((address_space(3))) void*)(smem + 4 * KT_BYTES + (j & 1) * 256),
-                                                     4, lane * 4, j * D * 2, 0, 0);
-    };
     // mean blocks of this (batch, KV head): block g serves tiles 16g .. 16g+15; one 1 KiB piece per wave (D = 64: waves 0-3)
     const int nblk16 = (ntile + 15) >> 4;
     const __amdgpu_buffer_rsrc_t kmbuf = __builtin_amdgcn_make_buffer_rsrc(
@@ -511,7 +510,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             copy_1k_to_lds<0>(kmbuf, g * KM_BYTES + wave * 1024, smem + 4 * KT_BYTES + wave * 1024, lane);
     };
     auto issue_k = [&](int j) {
-        issue_k0(j);
         const int src = j * TILE_BYTES;
         char* dst = smem + (j & 1) * KT_BYTES;
 #pragma unroll
@@ -568,7 +566,6 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
         constexpr int piece = decltype(piece_c)::value;       // 0 .. 2*CPW-1: K' pieces first, then V pieces
         const int jl = sg >> 1;
         if (piece < CPW) {
-            if (piece == 0 && jl + 1 < J_wg) issue_k0(jl + 1);
             if (jl + 1 < J_wg)
                 copy_1k_to_lds<(piece % CPW) * 1024>(wsbuf, (jl + 1) * TILE_BYTES + wave * (CPW * 1024),
                                                      smem + ((jl + 1) & 1) * KT_BYTES + wave * (CPW * 1024), lane);
@@ -612,7 +609,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // Hand-offs between the parts of one wave.
     constexpr bool LAZY = !STRICT;   // fp32 variants: the recovering factor goes to P, not to the stored output
     constexpr float CMAX = 8.f;      // LAZY: P may exceed 1 by at most e^CMAX before the row re-references its scale
-    float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile whose S' was computed last
+    float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile in the vector part
 
     // Both GEMMs run k-step by k-step: the four MFMAs of a k-step share their B operand (the Q or P fragment) and go
     // to the four accumulator blocks in turn, so consecutive MFMAs never depend on each other and the B registers are
@@ -623,29 +620,17 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #endif
     constexpr int PF = PASA_PF;
     constexpr int NM1 = 4 * KS;      // MFMAs of the first GEMM:  n = kb * KS + ks
-    constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM: n = cb * 8 + kk
+    constexpr int NM2 = CB * 8;      // MFMAs of the second GEMM
     auto gemm1 = [&](int jt) {   // S'^T of tile jt: 128 keys x 32 queries; MFMA n: key block n % 4, k-step n / 4
         const _Float16* lds_k = reinterpret_cast<const _Float16*>(smem + (jt & 1) * KT_BYTES);
         auto frag = [&](int n) { return *reinterpret_cast<const h8*>(lds_k + ((2 * (n / 4) + lh) * T + 32 * (n % 4) + lq) * 8); };
         h8 a[PF];
 #pragma unroll
         for (int n = 0; n < PF; ++n) a[n] = frag(n);
-        if (DIRECT) {
-            // q . k0 on the matrix core: k0 is row 0 of an otherwise zero 32-row A operand, accumulated in the block
-            // of S' that is written last; row 0 of the result sits in element 0 of lanes 0-31
-            const _Float16* lds_k0 = reinterpret_cast<const _Float16*>(smem + 4 * KT_BYTES + (jt & 1) * 256);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                h8 ak = (h8)(_Float16)0;
-                if (lq == 0) ak = *reinterpret_cast<const h8*>(lds_k0 + (2 * ks + lh) * 8);
-                S[3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ak, Qf[ks], ks ? S[3] : (f16v)0.f, 0, 0, 0);
-            }
-        }
         PASA_FENCE();
 #pragma unroll
         for (int n = 0; n < NM1; ++n) {
             const int kb = n % 4, ks = n / 4;
-            if (DIRECT && n == 3) cj = scale * sum32(S[3][0]);      // before the last block's first MFMA reuses S[3]
             if (ks == 0)
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[n % PF], Qf[ks], (f16v)0.f, 0, 0, 0);
             else
@@ -750,9 +735,9 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             // ---- pseudo-average over all 128 keys of the tile (before masking) ----
             float sbar = 0.f;
             if (MSBAR) {
-                // stored per 128 key slots; a ragged last tile divides by its own key count
                 const float v = reinterpret_cast<const float*>(smem + SB_OFF + wave * 2048)[(j & 15) * 32 + lq];
-                sbar = tail ? v * ((float)T * inv_tail) : v;
+                if (DIRECT) cj = scale * v;                    // the bias the shift removed from this tile's scores
+                else sbar = tail ? v * ((float)T * inv_tail) : v;   // stored per 128 key slots; a ragged last tile divides by its own key count
             } else if (!NAIVE && !DIRECT) {
                 float ps[4];
 #pragma unroll
@@ -1061,7 +1046,7 @@ template <int D, int VAR, bool CAUSAL, bool INSTR>
 hipError_t launch_fwd(const PasaLaunch& p)
 {
     constexpr int RWG = 256;
-    constexpr int LDS_BYTES = 4 * (T * D * 2) + (VAR == PASA_K_DIRECT ? 512 : 0) + (VAR == PASA_K_MIXED ? 64 * D + 8 * 2048 : 0);
+    constexpr int LDS_BYTES = 4 * (T * D * 2) + ((VAR == PASA_K_MIXED || VAR == PASA_K_DIRECT) ? 64 * D + 8 * 2048 : 0);
     const int nqt = (p.Nq + RWG - 1) / RWG;
     const int nsplit = (VAR == PASA_K_STRICT16 || p.nsplit < 1) ? 1 : p.nsplit;   // fp16 state has no merge rule
     const dim3 grid((unsigned)(nqt * p.Hq * p.B * nsplit));
@@ -1078,7 +1063,7 @@ hipError_t launch_fwd(const PasaLaunch& p)
         lds_limit_set.fetch_or(bit, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, grid, dim3(512), LDS_BYTES, p.stream, (const _Float16*)p.q, (const char*)p.ws,
-                       (_Float16*)p.o, (const _Float16*)p.k0, (const _Float16*)p.kmean, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
+                       (_Float16*)p.o, (const _Float16*)p.kmean, p.Hq, p.Hkv, p.Nq, p.row0, p.N, nqt, p.inva, p.scale, p.io_bf16, p.overflow_s,
                        nsplit > 1 ? nullptr : p.nonfinite_o, p.overflow_group, p.gate, nsplit,
                        nsplit > 1 ? (float*)p.part_o : nullptr, nsplit > 1 ? (double*)p.part_lr : nullptr);
     e = hipGetLastError();
