@@ -152,7 +152,7 @@ int pasa_attn_fwd_static(const void* q, const void* k, const void* v, void* o,
 int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, float scale,
                     const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
 int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
-                           const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
+                           const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
 
 /* The main loops of Algorithm 1 for a chunk of queries against a prepared workspace of N keys (the problem
  * statement of section 1.1 allows different query and key lengths S1 != S2; the paper does not elaborate).
@@ -164,7 +164,7 @@ int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N
  * output, any other split the same up to the fp32 summation order of the pseudo-average.  PASA_EINVAL for
  * Nq <= 0 or row0 < 0; otherwise the rules of pasa_attn_fwd_prepared. */
 int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
-                        float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream);
+                        float scale, const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream);
 
 /* An adaptive start of PASA (the paper's closing section names it as future work and gives no mechanism; this is
  * a simple one).  Pass 1 runs the partially low-precision FlashAttention without any shift (PASA_NAIVE16: raw

@@ -371,7 +371,7 @@ int pasa_prepare_kv(const void* k, const void* v, int B, int Hkv, int N, int d, 
 }
 
 int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N, int d, int causal, float scale,
-                           const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
+                           const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream)
 {
     return pasa_attn_fwd_chunk(q, o, B, Hq, Hkv, N, 0, N, d, causal, scale, opts, workspace, workspace_bytes, stream);
 }
@@ -381,7 +381,7 @@ int pasa_attn_fwd_prepared(const void* q, void* o, int B, int Hq, int Hkv, int N
 namespace {
 
 int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
-                   float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream,
+                   float scale, const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream,
                    unsigned long long* overflow_group, const unsigned long long* gate)
 {
     if (q == nullptr || o == nullptr || !aligned(q, 16) || !aligned(o, 16) || o == q) return PASA_EINVAL;
@@ -416,7 +416,7 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     const size_t rows_all = (size_t)B * Hq * Nq, room = workspace_bytes - need;
     while (ns > 1 && (size_t)ns * rows_all * split_row_bytes(d) > room) --ns;
     p.nsplit = ns;
-    char* split_base = static_cast<char*>(const_cast<void*>(workspace)) + need;
+    char* split_base = static_cast<char*>(workspace) + need;
     p.part_lr = split_base;                                              // [ns][rows][2] doubles
     p.part_o = split_base + (size_t)ns * rows_all * 16;                  // [ns][rows][d] floats
     p.stream = static_cast<hipStream_t>(stream);
@@ -428,7 +428,7 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
 extern "C" {
 
 int pasa_attn_fwd_chunk(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int row0, int N, int d, int causal,
-                        float scale, const pasa_opts* opts, const void* workspace, size_t workspace_bytes, void* stream)
+                        float scale, const pasa_opts* opts, void* workspace, size_t workspace_bytes, void* stream)
 {
     return fwd_chunk_impl(q, o, B, Hq, Hkv, Nq, row0, N, d, causal, scale, opts, workspace, workspace_bytes, stream,
                           nullptr, nullptr);

@@ -16,7 +16,7 @@ import pytest
 import paper_2503_01873_amd as P
 from oracle import pasa_oracle as po
 from workloads import Workload, workload, gen_full, gen_q_head, gen_kv_head
-from gpu_harness import gpu_attn, gpu_attn_chunks, compare, f32, ORACLE_POLICY, VARIANT_NAME
+from gpu_harness import bf16_bits, gpu_attn, gpu_attn_chunks, compare, f32, ORACLE_POLICY, VARIANT_NAME
 
 pytestmark = pytest.mark.gpu
 
@@ -555,6 +555,35 @@ def test_key_split_against_the_oracle_and_against_one_workgroup_per_tile(Nq, N, 
     print(VARIANT_NAME[variant], Nq, N, "split vs oracle", c, "| unsplit vs oracle", cw, "| split vs unsplit", cs)
     assert (c["maxabs"] <= 2e-3) if variant != P.S16 else (c["p999"] <= 2e-3)
     assert cs["maxabs"] <= 2e-3
+
+
+def test_key_split_bf16_and_counters():
+    """The merge kernel writes the output: bf16 conversion and the non-finite counter live there when the keys are split."""
+    import torch
+    rng = np.random.default_rng(931)
+    B, Hq, Hkv, Nq, N, d = 1, 2, 1, 64, 2304, 128
+    q = po.fl(rng.standard_normal((B, Hq, Nq, d)), "bf16").astype(np.float32)
+    k = po.fl(rng.standard_normal((B, Hkv, N, d)) + 3, "bf16").astype(np.float32)
+    v = po.fl(rng.standard_normal((B, Hkv, N, d)), "bf16").astype(np.float32)
+    scale = f32(d ** -0.5)
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(bf16_bits(x).view(np.float16)).to(dev) for x in (q, k, v))
+    wsb = P.pasa_attn_fwd_workspace(B, Hq, Hkv, N, d)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    to = torch.full_like(tq, float("nan"))
+    cnt = torch.zeros(2, dtype=torch.int64, device=dev)
+    P.pasa_prepare_kv(tk, tv, B, Hkv, N, d, scale, ws, wsb, io_dtype=P.IO_BF16)
+    P.pasa_attn_fwd_chunk(tq, to, B, Hq, Hkv, Nq, N - Nq, N, d, True, scale, ws, wsb, io_dtype=P.IO_BF16,
+                          overflow_s=cnt[0:1], nonfinite_o=cnt[1:2])
+    torch.cuda.synchronize()
+    o = (to.cpu().numpy().view(np.uint16).astype(np.uint32) << 16).view(np.float32)
+    qh, kh, vh = po.from_bf16(q), po.from_bf16(k), po.from_bf16(v)
+    ref = np.stack([[po.pasa_rows(qh[b, h], kh[b, 0], vh[b, 0], scale, True, BETA, 128, po.MIXED, N - Nq, out_fmt="bf16")
+                     for h in range(Hq)] for b in range(B)])
+    assert np.isfinite(o).all() and cnt.tolist() == [0, 0]
+    c = compare(o, ref)
+    print(c)
+    assert c["maxabs"] <= 8e-3 and c["p999"] <= 4e-3        # one bf16 step of an output in [1, 2) is 7.8e-3
 
 
 # ------------------------------------------------------------------ direct-bias recovery (PASA_DIRECT, not the paper's step)

@@ -61,6 +61,27 @@ def test_static_entry_point_two_calls_second_smaller(variant):
         assert err2 <= 2e-3, err2
 
 
+def test_static_entry_point_with_a_key_split():
+    """Few query heads and many keys: the call splits the keys, with its partial results in what the fixed regions
+    leave of the library's array.  (Not compared bit for bit with pasa_attn_fwd_ex here: given another amount of
+    workspace that call may split another number of ways, which changes the rounding, not the result.)"""
+    import torch
+    dev = torch.device("cuda:0")
+    q, k, v = _inputs(13, 1, 2, 1, 2200, 64)
+    scale = float(np.float32(1.0 / 8.0))
+    tq, tk, tv = (torch.from_numpy(x).to(dev) for x in (q, k, v))
+    outs = []
+    for _ in range(2):                       # twice: the second call finds the first one's partial results in the array
+        to = torch.full_like(tq, float("nan"))
+        P.pasa_attn_fwd_static(tq, tk, tv, to, 1, 2, 1, 2200, 64, True, scale, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        outs.append(to.cpu().numpy())
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+    ref = po.pasa_bhnd(q, k, v, scale, True, po.default_beta(), 128, po.MIXED)
+    err = np.abs(outs[0].astype(np.float64) - ref.astype(np.float64)).max()
+    assert np.isfinite(outs[0]).all() and err <= 2e-3, err
+
+
 def test_static_entry_point_refuses_what_does_not_fit():
     import torch
     dev = torch.device("cuda:0")
