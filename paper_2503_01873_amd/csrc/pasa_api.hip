@@ -112,10 +112,10 @@ double pasa_optimal_beta(double beta0, int n, int tp)
 
 namespace {
 
-// Workspace layout: the K'/V tiles, then (used by PASA_DIRECT only) one fp16 shift vector of d halfs per tile, then
-// (used by the adaptive entry point only) one 64-bit overflow counter per (batch, KV head), then (used by PASA_MIXED
-// only) one mean block of 32 x d halfs per 16 key tiles, then the region of the key split: per split and query row the
-// stored output (d floats) and two doubles (sum, level).
+// Workspace layout: the K'/V tiles, then (written by PASA_DIRECT's pre-processing) one fp16 shift vector of d halfs per
+// tile in plain order, then (used by the adaptive entry point only) one 64-bit overflow counter per (batch, KV head),
+// then one block of 32 x d halfs per 16 key tiles (PASA_MIXED: the tiles' mean keys; PASA_DIRECT: their shift vectors),
+// then the region of the key split: per split and query row two doubles (sum, level) and the stored output (d floats).
 size_t tiles_bytes(int B, int Hkv, int N, int d)
 {
     const size_t ntile = ((size_t)N + kShiftTile - 1) / kShiftTile;      // a ragged last tile is padded
@@ -153,6 +153,7 @@ size_t workspace_min_bytes(int B, int Hkv, int N, int d)
 
 // Key split.  A launch of fewer than 192 workgroups (256 query rows of one head each) leaves compute units idle; then
 // the key tiles of every workgroup are divided among up to 256 / workgroups of them, in pieces of 16 tiles, at most 16.
+constexpr int kComputeUnits = 256;      // MI355X
 constexpr int kSplitBelow = 192;
 constexpr int kMaxSplit = 16;
 constexpr size_t kSplitFloorBytes = (size_t)1 << 20;   // always there, so that short query chunks (decoding) can split
@@ -162,7 +163,7 @@ int wanted_splits(int B, int Hq, int Nq, int N)
     const long units = ((long)Nq + 255) / 256 * Hq * B;
     const int nblk16 = (int)((((long)N + kShiftTile - 1) / kShiftTile + 15) / 16);
     if (units >= kSplitBelow || nblk16 < 2) return 1;
-    long ns = 256 / units;
+    long ns = kComputeUnits / units;
     if (ns > nblk16) ns = nblk16;
     if (ns > kMaxSplit) ns = kMaxSplit;
     return ns < 2 ? 1 : (int)ns;
