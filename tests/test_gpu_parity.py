@@ -889,12 +889,14 @@ def test_adaptive_start_switches_only_the_kv_head_that_overflowed():
 
 # ------------------------------------------------------------------ capture into a HIP graph
 
-def test_graph_capture_and_replay():
+@pytest.mark.parametrize("N", [1000, 2500])
+def test_graph_capture_and_replay(N):
     """pasa_attn_fwd_ex with a caller workspace allocates nothing and only enqueues kernels, so it can be
-    captured into a HIP graph; every replay must give the eager result for the inputs then in the buffers."""
+    captured into a HIP graph; every replay must give the eager result for the inputs then in the buffers.
+    N = 2500: the call splits its keys (three kernels: pre-processing, main, merge)."""
     import torch
     dev = torch.device("cuda:0")
-    w = _small(3, 1000, Hq=4, Hkv=2)
+    w = _small(3, N, Hq=4, Hkv=2)
     scale = f32(w.scale)
     inputs = []
     for seed in (w.seed, w.seed + 1, w.seed + 2):
