@@ -119,26 +119,6 @@ size_t pasa_attn_fwd_workspace(int B, int Hq, int Hkv, int N, int d);
 /* The part of the workspace every call needs (all regions but the key split's). */
 size_t pasa_attn_fwd_workspace_min(int B, int Hkv, int N, int d);
 
-/* How a causal call of a few rounds of workgroups is laid out on the GPU (host logic; for tests and tools).  The
- * attention kernel has one work item per (256 query rows, query head); with causal masking their lengths run from one
- * or two key tiles to all of them (section 1.1's lower-triangular S), and when the item count is a small, awkward
- * multiple of the compute units (`places`) a launch of one workgroup per item ends unevenly.  For more than `places`
- * and at most 1280 items the library can launch `places` workgroups instead and give each a list of items, balanced
- * by total length within each XCD's share (item index % 8 stays the XCD, so a KV head's query heads keep their L2).
- * This call writes that plan: start[w] .. start[w + 1] - 1 index `item` for workgroup w (start has places + 1
- * entries, item up to 1280); *worst_load is the largest load of a workgroup in half tile-steps (an item counts its
- * tiles twice plus 4 for its start and end), *ordinary_load the same under dispatch in index order (either may be
- * NULL).  The library follows the plan only where it wins at least 3 % on these figures (the kernel that walks lists
- * is a little slower per tile).  Returns n > 0: n items planned and the plan is used; -n - 1: planned but not used;
- * 0: these sizes are never planned; -1: invalid arguments.  Nq, row0 as for pasa_attn_fwd_chunk.  Applies to causal
- * calls without counters of all variants but PASA_STRICT16; results are bit-identical with and without it. */
-int pasa_work_plan(int B, int Hq, int Hkv, int Nq, int row0, int N, int places, unsigned short* start,
-                   unsigned short* item, int* worst_load, int* ordinary_load);
-
-/* Turns the planned launches off (on == 0) or on again for the whole process; returns the previous setting.  For
- * measurements and tests. */
-int pasa_work_plan_enable(int on);
-
 /* As pasa_attn_fwd, with options and a caller-provided workspace (DEVICE pointer, 256-byte aligned,
  * pasa_attn_fwd_workspace() bytes -- at least pasa_attn_fwd_workspace_min(); contents on return are unspecified).  opts == NULL means
  * {beta = -1, PASA_MIXED, 128, NULL, NULL, PASA_SHIFT_MEAN, PASA_IO_F16}.  Performs no allocation. */

@@ -57,11 +57,6 @@ def lib() -> ctypes.CDLL:
     L.pasa_attn_fwd_workspace.restype = sz
     L.pasa_attn_fwd_workspace_min.argtypes = [ci, ci, ci, ci]
     L.pasa_attn_fwd_workspace_min.restype = sz
-    L.pasa_work_plan.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(ctypes.c_ushort), ctypes.POINTER(ctypes.c_ushort),
-                                 ctypes.POINTER(ci), ctypes.POINTER(ci)]
-    L.pasa_work_plan.restype = ci
-    L.pasa_work_plan_enable.argtypes = [ci]
-    L.pasa_work_plan_enable.restype = ci
     L.pasa_attn_fwd_ex.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp, sz, vp]
     L.pasa_attn_fwd_ex.restype = ci
     L.pasa_attn_fwd_static.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ctypes.POINTER(pasa_opts), vp]
@@ -138,25 +133,6 @@ def pasa_attn_fwd_workspace(B, Hq, Hkv, N, d) -> int:
 
 def pasa_attn_fwd_workspace_min(B, Hkv, N, d) -> int:
     return lib().pasa_attn_fwd_workspace_min(B, Hkv, N, d)
-
-
-def pasa_work_plan(B, Hq, Hkv, Nq, row0, N, places):
-    """The item lists of a planned causal launch: (lists, worst_load, ordinary_load, used) with lists[w] the work items
-    of workgroup w in order and `used` whether the library follows the plan; None when these sizes are never planned."""
-    start = (ctypes.c_ushort * (places + 1))()
-    item = (ctypes.c_ushort * 1280)()
-    worst, ordinary = ctypes.c_int(0), ctypes.c_int(0)
-    n = lib().pasa_work_plan(B, Hq, Hkv, Nq, row0, N, places, start, item, ctypes.byref(worst), ctypes.byref(ordinary))
-    if n == -1:
-        raise PasaError(1, "pasa_work_plan")
-    if n == 0:
-        return None
-    lists = [[int(item[i]) for i in range(start[w], start[w + 1])] for w in range(places)]
-    return lists, int(worst.value), int(ordinary.value), n > 0
-
-
-def pasa_work_plan_enable(on: bool) -> bool:
-    return bool(lib().pasa_work_plan_enable(1 if on else 0))
 
 
 def pasa_attn_fwd(q, k, v, o, B, Hq, Hkv, N, d, causal, scale, stream=None, check=True) -> int:

@@ -5,12 +5,7 @@
 #include <math.h>
 #include <stdint.h>
 
-#include <string.h>
-
-#include <algorithm>
-#include <atomic>
 #include <mutex>
-#include <vector>
 
 #include "pasa.h"
 #include "pasa_kernels.h"
@@ -156,190 +151,6 @@ size_t workspace_min_bytes(int B, int Hkv, int N, int d)
     return kmean_offset(B, Hkv, N, d) + kmean_bytes(B, Hkv, N, d);
 }
 
-// ---------------------------------------------------------------------------------------------
-// Work plan of a causal launch.  A launch has one work item per (256 query rows, head); causal items differ in length
-// (the last query tile sees all key tiles, the first one or two).  Dispatched one workgroup per item, longest first,
-// the chip's places finish unevenly when the item count is a small and awkward multiple of the places: 896 items of
-// 2 .. 64 tile-steps on 256 places end between 114 and 120 tile-steps where the mean is 115.5.  With few enough items
-// the host deals them out itself: per XCD class (index % 8 -- the map of items to XCDs, which keeps a KV head's
-// query heads on one L2, stays the ordinary launch's) the items go longest-first to the least loaded workgroup, then
-// pairs of items of different workgroups are exchanged while that lowers the sum of the squared loads.  A workgroup
-// runs its list one item behind the other.  Costs are in half tile-steps; an item costs its tiles plus kItemFixed for
-// its prologue, pipeline fill and drain, and epilogue (measured: about two tile-steps).
-// The kernel that walks a list is 1.5 - 3 % slower per tile than the ordinary one (measured; the item loop costs it
-// registers), so a plan is used only where it promises at least kPlanGainPercent against what dispatch in index order
-// would give (each item to the workgroup that is free first, simulated with the same costs): 8192 tokens of 28 heads
-// gain 1.6 % on paper and stay ordinary, 6144 tokens of 28 heads or 8192 of 20 heads gain 8 - 11 %.
-// ---------------------------------------------------------------------------------------------
-constexpr int kItemFixed = 4;
-constexpr int kPlanGainPercent = 3;
-std::atomic<int> g_plan_enabled{1};
-
-struct PlanKey {
-    int B, Hq, Hkv, Nq, row0, N, places;
-    bool operator==(const PlanKey& o) const
-    {
-        return B == o.B && Hq == o.Hq && Hkv == o.Hkv && Nq == o.Nq && row0 == o.row0 && N == o.N && places == o.places;
-    }
-};
-
-// query tile of work item i: the decode of the attention kernel
-int item_query_tile(int i, int nqt, int G, int ngroups)
-{
-    if (ngroups % 8 == 0) {
-        const int r = i >> 3, per = (ngroups >> 3) * G;
-        return nqt - 1 - r / per;
-    }
-    if (8 % ngroups == 0 && (nqt * G) % (8 / ngroups) == 0) {
-        const int span = 8 / ngroups, x = i & 7, r = i >> 3;
-        return nqt - 1 - (r * span + (x % span)) / G;
-    }
-    return nqt - 1 - i / (ngroups * G);
-}
-
-// false: no plan for these sizes (then the launch is an ordinary one).  *worst: the largest load of a workgroup under
-// the plan, *ordinary: under dispatch in index order.
-bool build_plan(const PlanKey& k, PasaPlan* plan, int* worst, int* ordinary)
-{
-    const int nqt = (k.Nq + 255) / 256, nitems = nqt * k.Hq * k.B;
-    if (k.places < 8 || k.places > kPasaPlanPlaces || nitems <= k.places || nitems > kPasaPlanItems) return false;
-    const int G = k.Hq / k.Hkv, ngroups = k.B * k.Hkv, ntile = (k.N + kShiftTile - 1) / kShiftTile;
-    std::vector<int> cost(nitems);
-    for (int i = 0; i < nitems; ++i) {
-        const int qt = item_query_tile(i, nqt, G, ngroups);
-        int last_row = qt * 256 + 255;
-        if (last_row > k.Nq - 1) last_row = k.Nq - 1;
-        int tiles = (k.row0 + last_row) / kShiftTile + 1;
-        if (tiles > ntile) tiles = ntile;
-        cost[i] = 2 * tiles + kItemFixed;
-    }
-    std::vector<std::vector<int>> list(k.places);
-    std::vector<long> load(k.places, 0);
-    std::vector<int> owner(nitems);
-    uint64_t rng = 0x9E3779B97F4A7C15ull;
-    auto next_rand = [&](int n) {
-        rng = rng * 6364136223846793005ull + 1442695040888963407ull;
-        return (int)((rng >> 33) % (uint64_t)n);
-    };
-    long ordinary_hi = 0;
-    for (int x = 0; x < 8; ++x) {
-        std::vector<int> items, wgs;
-        for (int i = x; i < nitems; i += 8) items.push_back(i);
-        for (int w = x; w < k.places; w += 8) wgs.push_back(w);
-        if (items.empty()) continue;
-        {   // dispatch in index order: each item to the place that is free first
-            std::vector<long> busy(wgs.size(), 0);
-            for (int i : items) *std::min_element(busy.begin(), busy.end()) += cost[i];
-            ordinary_hi = std::max(ordinary_hi, *std::max_element(busy.begin(), busy.end()));
-        }
-        std::stable_sort(items.begin(), items.end(), [&](int a, int b) { return cost[a] > cost[b]; });
-        for (int i : items) {                                   // longest first to the least loaded
-            int best = wgs[0];
-            for (int w : wgs)
-                if (load[w] < load[best]) best = w;
-            owner[i] = best;
-            load[best] += cost[i];
-        }
-        // Then random moves of one item, and exchanges of two, that do not raise the sum of the squared loads (equal
-        // counts as well, so that the walk leaves plateaus), until the loads are as even as the costs' common
-        // divisor allows.
-        const int n = (int)items.size(), nw = (int)wgs.size();
-        long step = 0;
-        for (int i : items) step = std::__gcd(step, (long)cost[i]);
-        if (step < 2) step = 2;
-        for (int it = 0; it < 100000; ++it) {
-            if ((it & 1023) == 0) {
-                long lo = load[wgs[0]], hi = lo;
-                for (int w : wgs) {
-                    lo = std::min(lo, load[w]);
-                    hi = std::max(hi, load[w]);
-                }
-                if (hi - lo <= step) break;
-            }
-            const int a = items[next_rand(n)], wa = owner[a];
-            int wb, b = -1;
-            long d = cost[a];
-            if (next_rand(10) < 3) {
-                wb = wgs[next_rand(nw)];
-            } else {
-                b = items[next_rand(n)];
-                wb = owner[b];
-                d -= cost[b];
-            }
-            if (wa == wb || d == 0) continue;
-            const long la = load[wa], lb = load[wb];
-            if ((la - d) * (la - d) + (lb + d) * (lb + d) <= la * la + lb * lb) {
-                owner[a] = wb;
-                if (b >= 0) owner[b] = wa;
-                load[wa] = la - d;
-                load[wb] = lb + d;
-            }
-        }
-    }
-    for (int i = 0; i < nitems; ++i) list[owner[i]].push_back(i);
-    int at = 0;
-    long hi = 0;
-    for (int w = 0; w < kPasaPlanPlaces; ++w) {
-        plan->start[w] = (unsigned short)at;
-        if (w >= k.places) continue;
-        std::stable_sort(list[w].begin(), list[w].end(), [&](int a, int b) { return cost[a] > cost[b]; });
-        for (int i : list[w]) plan->item[at++] = (unsigned short)i;
-        hi = std::max(hi, load[w]);
-    }
-    plan->start[kPasaPlanPlaces] = (unsigned short)at;
-    for (int i = at; i < kPasaPlanItems; ++i) plan->item[i] = 0;
-    if (worst != nullptr) *worst = (int)hi;
-    if (ordinary != nullptr) *ordinary = (int)ordinary_hi;
-    return true;
-}
-
-bool plan_pays(int worst, int ordinary) { return (long)worst * (100 + kPlanGainPercent) <= (long)ordinary * 100; }
-
-// The plans of the latest shapes are kept (a plan is a function of the sizes alone).
-struct PlanSlot {
-    PlanKey key;
-    int state;          // 0 empty, 1 no plan for these sizes, 2 plan
-    unsigned long long used;
-    PasaPlan plan;
-};
-std::mutex g_plan_mutex;
-PlanSlot g_plans[8];
-unsigned long long g_plan_clock = 0;
-
-bool lookup_plan(const PlanKey& k, PasaPlan* out)
-{
-    std::lock_guard<std::mutex> lock(g_plan_mutex);
-    for (PlanSlot& s : g_plans)
-        if (s.state != 0 && s.key == k) {
-            s.used = ++g_plan_clock;
-            if (s.state == 2) memcpy(out, &s.plan, sizeof(PasaPlan));
-            return s.state == 2;
-        }
-    PlanSlot* victim = &g_plans[0];                 // an empty slot, else the one used longest ago
-    for (PlanSlot& s : g_plans)
-        if (s.state == 0 || (victim->state != 0 && s.used < victim->used)) victim = &s;
-    victim->key = k;
-    victim->used = ++g_plan_clock;
-    int worst = 0, ordinary = 0;
-    victim->state = (build_plan(k, &victim->plan, &worst, &ordinary) && plan_pays(worst, ordinary)) ? 2 : 1;
-    if (victim->state == 2) memcpy(out, &victim->plan, sizeof(PasaPlan));
-    return victim->state == 2;
-}
-
-// compute units of the current device (0: unknown)
-int device_places()
-{
-    static std::atomic<int> cached[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
-    int n = cached[dev & 63].load(std::memory_order_acquire);
-    if (n == 0) {
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
-        cached[dev & 63].store(n, std::memory_order_release);
-    }
-    return n;
-}
-
 // Key split.  A launch of fewer than 192 workgroups (256 query rows of one head each) leaves compute units idle; then
 // the key tiles of every workgroup are divided among up to 256 / workgroups of them, in pieces of 16 tiles, at most 16.
 constexpr int kComputeUnits = 256;      // MI355X
@@ -382,28 +193,6 @@ size_t pasa_attn_fwd_workspace_min(int B, int Hkv, int N, int d)
 {
     if (check_shape(B, Hkv, Hkv, N, d) != PASA_OK) return 0;
     return workspace_min_bytes(B, Hkv, N, d);
-}
-
-int pasa_work_plan(int B, int Hq, int Hkv, int Nq, int row0, int N, int places, unsigned short* start,
-                   unsigned short* item, int* worst_load, int* ordinary_load)
-{
-    if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Nq <= 0 || row0 < 0 || N <= 0 || places <= 0) return -1;
-    if (start == nullptr || item == nullptr) return -1;
-    PasaPlan plan;
-    int worst = 0, ordinary = 0;
-    if (!build_plan(PlanKey{B, Hq, Hkv, Nq, row0, N, places}, &plan, &worst, &ordinary)) return 0;
-    const int n = plan.start[kPasaPlanPlaces];
-    for (int w = 0; w <= places; ++w) start[w] = w < kPasaPlanPlaces ? plan.start[w] : (unsigned short)n;
-    start[places] = (unsigned short)n;
-    for (int i = 0; i < n; ++i) item[i] = plan.item[i];
-    if (worst_load != nullptr) *worst_load = worst;
-    if (ordinary_load != nullptr) *ordinary_load = ordinary;
-    return plan_pays(worst, ordinary) ? n : -n - 1;
-}
-
-int pasa_work_plan_enable(int on)
-{
-    return g_plan_enabled.exchange(on ? 1 : 0);
 }
 
 }  // extern "C"
@@ -632,19 +421,6 @@ int fwd_chunk_impl(const void* q, void* o, int B, int Hq, int Hkv, int Nq, int r
     p.part_lr = split_base;                                              // [ns][rows][2] doubles
     p.part_o = split_base + (size_t)ns * rows_all * 16;                  // [ns][rows][d] floats
     p.stream = static_cast<hipStream_t>(stream);
-    // causal launches of a few rounds of workgroups: the host deals the work items out (see build_plan)
-    p.plan = nullptr;
-    p.plan_places = 0;
-    PasaPlan plan;
-    if (causal && ns == 1 && gate == nullptr && pr.variant != PASA_STRICT16 && pr.overflow_s == nullptr &&
-        pr.nonfinite_o == nullptr && g_plan_enabled.load(std::memory_order_relaxed)) {
-        const int places = device_places();
-        const PlanKey key{B, Hq, Hkv, Nq, p.row0, N, places};
-        if (places > 0 && lookup_plan(key, &plan)) {
-            p.plan = &plan;
-            p.plan_places = places;
-        }
-    }
     return pasa_launch_fwd(p) == hipSuccess ? PASA_OK : PASA_ELAUNCH;
 }
 

@@ -9,16 +9,6 @@ enum { PASA_K_MIXED = 0, PASA_K_STRICT16 = 1, PASA_K_NAIVE16 = 2, PASA_K_S16 = 3
 // how the pre-processing kernel forms K'
 enum { PASA_PREP_MEAN = 0, PASA_PREP_MATRIX = 1, PASA_PREP_DIRECT = 2 };
 
-// Work plan of a launch with fewer workgroups than work items: workgroup w runs the items item[start[w]] ..
-// item[start[w + 1] - 1] (indices as the workgroups of an ordinary launch have them), one behind the other.  It travels
-// as a kernel argument, which bounds its size.
-constexpr int kPasaPlanPlaces = 256;
-constexpr int kPasaPlanItems = 1280;
-struct PasaPlan {
-    unsigned short start[kPasaPlanPlaces + 1];
-    unsigned short item[kPasaPlanItems];
-};
-
 struct PasaLaunch {
     const void* q;
     const void* ws;   // per (batch, KV head, key tile): shifted-key tile then value tile, fragment-major layout
@@ -42,8 +32,6 @@ struct PasaLaunch {
                       // and are merged by a second kernel; ignored by PASA_K_STRICT16
     void* part_o;
     void* part_lr;
-    const PasaPlan* plan;   // host pointer or null.  Non-null (causal, no counters, no gate, nsplit <= 1, not
-    int plan_places;        // PASA_K_STRICT16): plan_places workgroups are launched and follow the plan
     hipStream_t stream;
 };
 
