@@ -622,6 +622,16 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     // Hand-offs between the parts of one wave.
     constexpr bool LAZY = !STRICT;   // fp32 variants: the recovering factor goes to P, not to the stored output
+    // d = 64: the vector part is 2.7 times as long as the matrix part (the softmax is the same work, the GEMMs half),
+    // so the running sum moves to the idle matrix core: one more MFMA per k-step of the second GEMM, P^T against a
+    // block of ones, accumulates the row sums of P beside the stored output, at the same scale (every row of the
+    // result is the sum; 64 additions per tile and lane leave the vector part).
+#ifndef PASA_LSUM_MFMA_128
+#define PASA_LSUM_MFMA_128 0
+#endif
+    constexpr bool LSUM_MFMA = LAZY && (D == 64 || PASA_LSUM_MFMA_128);
+    f16v Lacc = (f16v)0.f;
+    const h8 ones = (h8)(_Float16)1;
     constexpr float CMAX = 8.f;      // LAZY: P may exceed 1 by at most e^CMAX before the row re-references its scale
     float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile in the vector part
 
@@ -671,6 +681,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
             PASA_FENCE();
             if (n + PF < NM2) a[n % PF] = frag(n + PF);
             PASA_FENCE();
+            if (LSUM_MFMA && cb == CB - 1) {
+                Lacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ones, Pf[kk], Lacc, 0, 0, 0);
+                PASA_FENCE();
+            }
         }
     };
 
@@ -894,9 +908,13 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 #pragma unroll
                     for (int i = 0; i < 16; ++i) O[cb][i] *= r;
                 l *= r;
+                if (LSUM_MFMA) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) Lacc[i] *= r;
+                }
             }
             // ---- P = exp(S' - m' [+ c]) rounded to fp16; l' = sum of the rounded P ----
-            float lsum;
+            float lsum = 0.f;
             {
                 const float nml = (c_adj - mref) * LOG2E;
                 float pl[4];
@@ -918,10 +936,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         const h2 p2 = pack_rn(e0, e1);
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3)] = p2[0];
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
-                        pl[kb] = (STRICT || MSBAR) ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
+                        if (!LSUM_MFMA) pl[kb] = (STRICT || MSBAR) ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
                     }
                 }
-                lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
+                if (!LSUM_MFMA) lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
                 if (STRICT) lsum = (float)(_Float16)lsum;
             }
 
@@ -940,6 +958,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     }
     if (grp == 0) __syncthreads();         // group B's last barrier
 
+    if (LSUM_MFMA) l = Lacc[0];            // every row of the block is the sum
     // ---------------- key split: leave the row state for the merge ----------------
     if (!STRICT && part_o != nullptr) {
         if (wave_valid) {
