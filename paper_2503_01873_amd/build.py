@@ -48,21 +48,5 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     return out
 
 
-PROBE = os.path.join(PKG, "dispatch_probe")
-
-
-def build_probe(verbose: bool = False) -> str:
-    """The stand-alone measurement tool csrc/dispatch_probe.hip (how the GPU hands workgroups out); not part of libpasa."""
-    cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           os.path.join(CSRC, "dispatch_probe.hip"), "-o", PROBE]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build(verbose=True, extra_flags=sys.argv[1:]))
-    print(build_probe(verbose=True))
