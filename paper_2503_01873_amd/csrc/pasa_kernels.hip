@@ -622,16 +622,20 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
 
     // Hand-offs between the parts of one wave.
     constexpr bool LAZY = !STRICT;   // fp32 variants: the recovering factor goes to P, not to the stored output
+    // The running sum l of the fp32 variants is not taken in the vector part that makes P.
+    // d = 128: the row sums of a tile's P are added up in the matrix part that follows, between the MFMAs of the second
+    // GEMM (which reads the same P fragments): the wave has issue slots to spare there (an MFMA occupies the matrix core
+    // for 32 cycles), while in the vector part every instruction counts.  0.7 % on the headline workload, although the
+    // vector part loses 64 of its 330 instructions: the kernel's clock, not its cycle count, is the limit.
     // d = 64: the vector part is 2.7 times as long as the matrix part (the softmax is the same work, the GEMMs half),
-    // so the running sum moves to the idle matrix core: one more MFMA per k-step of the second GEMM, P^T against a
-    // block of ones, accumulates the row sums of P beside the stored output, at the same scale (every row of the
-    // result is the sum; 64 additions per tile and lane leave the vector part).
-#ifndef PASA_LSUM_MFMA_128
-#define PASA_LSUM_MFMA_128 0
-#endif
-    constexpr bool LSUM_MFMA = LAZY && (D == 64 || PASA_LSUM_MFMA_128);
+    // and the sum moves onto the idle matrix core itself: one more MFMA per k-step of the second GEMM, P^T against a
+    // block of ones, accumulates the row sums beside the stored output, at the same scale (every row of the result is
+    // the sum).  4 % on the d = 64 workload (the first way is 2 % slower there; this way is 2.4 % slower at d = 128).
+    constexpr bool LSUM_MFMA = LAZY && D == 64;
+    constexpr bool LSUM_DEFER = LAZY && D == 128;
     f16v Lacc = (f16v)0.f;
     const h8 ones = (h8)(_Float16)1;
+    float pl_d[4] = {0.f, 0.f, 0.f, 0.f};
     constexpr float CMAX = 8.f;      // LAZY: P may exceed 1 by at most e^CMAX before the row re-references its scale
     float cj = 0.f;                  // DIRECT: scale * (q . k0) of the tile in the vector part
 
@@ -685,6 +689,21 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                 Lacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ones, Pf[kk], Lacc, 0, 0, 0);
                 PASA_FENCE();
             }
+            if (LSUM_DEFER) {
+                // 32 packed pairs over NM2 MFMAs
+                constexpr int PER = 32 / NM2;
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int pr = n * PER + u;          // pair pr: Pf[pr / 4], elements 2 * (pr % 4), + 1
+                    const h2 p2 = {Pf[pr / 4][2 * (pr % 4)], Pf[pr / 4][2 * (pr % 4) + 1]};
+                    pl_d[pr & 3] = add_pair_mix(p2, pl_d[pr & 3]);
+                }
+                PASA_FENCE();
+            }
+        }
+        if (LSUM_DEFER) {
+            l += sum32((pl_d[0] + pl_d[1]) + (pl_d[2] + pl_d[3]));
+            pl_d[0] = pl_d[1] = pl_d[2] = pl_d[3] = 0.f;
         }
     };
 
@@ -936,10 +955,10 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
                         const h2 p2 = pack_rn(e0, e1);
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3)] = p2[0];
                         Pf[2 * kb + (t2 >> 2)][2 * (t2 & 3) + 1] = p2[1];
-                        if (!LSUM_MFMA) pl[kb] = (STRICT || MSBAR) ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
+                        if (!LSUM_MFMA && !LSUM_DEFER) pl[kb] = (STRICT || MSBAR) ? add_pair_mix(p2, pl[kb]) : add_pair(p2, pl[kb]);
                     }
                 }
-                if (!LSUM_MFMA) lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
+                if (!LSUM_MFMA && !LSUM_DEFER) lsum = sum32((pl[0] + pl[1]) + (pl[2] + pl[3]));
                 if (STRICT) lsum = (float)(_Float16)lsum;
             }
 
