@@ -626,13 +626,14 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // d = 128: the row sums of a tile's P are added up in the matrix part that follows, between the MFMAs of the second
     // GEMM (which reads the same P fragments): the wave has issue slots to spare there (an MFMA occupies the matrix core
     // for 32 cycles), while in the vector part every instruction counts.  0.7 % on the headline workload, although the
-    // vector part loses 64 of its 330 instructions: the kernel's clock, not its cycle count, is the limit.
+    // vector part loses 64 of its 330 instructions: the kernel's clock, not its cycle count, is the limit.  (MIXED and
+    // DIRECT; S16 and NAIVE16, whose vector part sums with v_dot2_f32_f16, lose 1.2 % by it and keep their sums there.)
     // d = 64: the vector part is 2.7 times as long as the matrix part (the softmax is the same work, the GEMMs half),
     // and the sum moves onto the idle matrix core itself: one more MFMA per k-step of the second GEMM, P^T against a
     // block of ones, accumulates the row sums beside the stored output, at the same scale (every row of the result is
     // the sum).  4 % on the d = 64 workload (the first way is 2 % slower there; this way is 2.4 % slower at d = 128).
     constexpr bool LSUM_MFMA = LAZY && D == 64;
-    constexpr bool LSUM_DEFER = LAZY && D == 128;
+    constexpr bool LSUM_DEFER = LAZY && D == 128 && MSBAR;
     f16v Lacc = (f16v)0.f;
     const h8 ones = (h8)(_Float16)1;
     float pl_d[4] = {0.f, 0.f, 0.f, 0.f};
