@@ -33,10 +33,14 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "pasa_fwd_qwen2_gqa_n8192_hbm_traf
 
 
 def kernel_source_hash():
+    """Hash of the kernel source as the compiler sees it: `//` comments and blank space do not count."""
     import hashlib
     h = hashlib.sha256()
-    with open(os.path.join(ROOT, "paper_2503_01873_amd", "csrc", "pasa_kernels.hip"), "rb") as f:
-        h.update(f.read())
+    with open(os.path.join(ROOT, "paper_2503_01873_amd", "csrc", "pasa_kernels.hip"), "r") as f:
+        for line in f:
+            code = " ".join(line.split("//")[0].split())
+            if code:
+                h.update(code.encode() + b"\n")
     return h.hexdigest()[:16]
 
 

@@ -441,7 +441,7 @@ void pasa_fwd(const _Float16* __restrict__ q, const char* __restrict__ ws, _Floa
     // How the workgroups of a launch reach the compute units was measured with a probe kernel (workgroups of this
     // kernel's LDS size that record their XCC, shader engine and compute unit and spin for a given time): within an XCD
     // they go to its four shader engines in strict rotation, in index order, and each waits for a compute unit of ITS
-    // engine (8 per engine); a simulation of exactly that reproduces the probe's end time to 0.1 %.  With the items
+    // engine (8 per engine); a simulation of exactly that reproduces the probe's end times to 0.4 %.  With the items
     // simply longest first the engine that always gets the first of four carries 5 % more than the one that gets the
     // last (896 causal items of 2 .. 64 tile-steps end 4.5 % behind the mean).  So every other group of four
     // consecutive places of an XCD's list is taken backwards: the engines' loads even out and items that are
